@@ -1,0 +1,260 @@
+/*
+ * blitz_layer.h — C ABI of the single-GPU share of live, layer-level model scaling.
+ *
+ * The paper scales a serving instance by sending it the model one layer at a time and lets the
+ * instance execute whatever prefix of layers it already holds, handing the activation to a fully
+ * loaded instance at a layer boundary (section 4, "Realizing live autoscale"; section 5.2, "Live
+ * autoscale protocol with paired instances").  On one MI355X that becomes:
+ *
+ *   - an *instance*: a weight arena for L decoder layers, a KV cache, two HIP streams;
+ *   - *layer ingest*: copy layer i's parameter blob from pinned host memory into HBM in chunks
+ *     on the copy stream, mark completion with a per-layer event (the host-memory source of
+ *     section 1 / section 5.3's parameter pool, overlapped with execution as in section 4);
+ *   - the *frontier*: how many leading layers are resident (an instance "can only execute layers
+ *     with parameters loaded", section 1, challenges);
+ *   - *run layers [a,b)* on a packed batch of hidden states with prefill and/or decode sequences
+ *     (section 2.1, layer-by-layer execution with a KV cache held in GPU memory), each layer
+ *     gated on its own ingest event;
+ *   - *boundary export / import*: the activation hand-off between instances (section 4).
+ *
+ * The arithmetic of a layer is the Llama-family decoder layer (RMSNorm, QKV projection, rotary
+ * embedding, causal attention with grouped KV heads, output projection, SwiGLU MLP, pre-norm
+ * residuals, no biases); the paper leaves it to its kernel library.
+ *
+ * Conventions
+ *   - All functions return 0 (BZ_OK) or a negative bz_status; none throws, none aborts.
+ *   - "device" pointers are HIP device addresses on the current device; "host" pointers are
+ *     ordinary host addresses; "pinned" means page-locked host memory (hipHostMalloc).
+ *   - Activations are bf16 (2 bytes, row-major).  In the fp32 debug build of the library
+ *     (bz_build_info() & BZ_BUILD_FP32_DEBUG) activations and the KV cache are float32; weights
+ *     stay bf16 in both builds.
+ *   - Work is enqueued on the instance's streams and completes asynchronously; bz_sync() or the
+ *     caller's own stream synchronisation makes results visible.
+ *   - An instance is not thread-safe: call it from one host thread at a time.
+ */
+#ifndef BLITZ_LAYER_H
+#define BLITZ_LAYER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum bz_status {
+    BZ_OK = 0,
+    BZ_EINVAL = -1,      /* bad argument (null, out of range, wrong size, misaligned) */
+    BZ_ENOMEM = -2,      /* allocation failed or a caller-provided arena is too small */
+    BZ_EBUSY = -3,       /* layer already loading or resident */
+    BZ_ENOTLOADED = -4,  /* a layer in [a,b) was never requested with bz_load_layer */
+    BZ_ENOTREADY = -5,   /* BZ_RUN_NOWAIT and a layer in [a,b) has not finished loading */
+    BZ_EHIP = -6,        /* a HIP runtime call failed; see bz_last_hip_error() */
+    BZ_ECAPACITY = -7,   /* KV arena / slot capacity / max_tokens / max_seq_len exceeded */
+    BZ_ESTATE = -8,      /* call not valid in this state (e.g. dry-run instance, slot not reserved) */
+} bz_status;
+
+enum {
+    BZ_FLAG_DRY_RUN = 1,        /* bz_create: build host-side state only, touch no GPU.  Calls that
+                                   would enqueue GPU work validate their arguments and then return
+                                   BZ_ESTATE. */
+};
+enum {
+    BZ_RUN_NOWAIT = 1,          /* bz_run_layers: fail with BZ_ENOTREADY instead of waiting on ingest */
+};
+enum {
+    BZ_BUILD_FP32_DEBUG = 1,
+};
+
+typedef struct bz_instance bz_instance;
+typedef struct bz_batch bz_batch;
+
+/* Model shape, capacities and (optionally) caller-owned resources.  Plain data. */
+typedef struct bz_config {
+    int32_t n_layers;        /* L >= 1 */
+    int32_t hidden;          /* H, multiple of 8 */
+    int32_t n_q_heads;       /* Hq */
+    int32_t n_kv_heads;      /* Hkv, divides Hq; Hq/Hkv in {1,2,4,8} */
+    int32_t head_dim;        /* d: 64 or 128 */
+    int32_t ffn;             /* F, multiple of 8 */
+    float   rms_eps;
+    float   rope_base;
+    int32_t max_seqs;        /* number of KV slots */
+    int32_t max_seq_len;     /* largest sequence length (positions 0..max_seq_len-1) */
+    int32_t max_tokens;      /* largest number of packed rows T in one bz_run_layers call */
+    int32_t flags;           /* BZ_FLAG_* */
+    int64_t kv_tokens;       /* KV arena capacity, in tokens per layer, shared by all slots */
+    int64_t chunk_bytes;     /* ingest chunk size; 0 selects the default (32 MiB) */
+    void*   compute_stream;  /* hipStream_t for kernels, or NULL: the library creates one */
+    void*   copy_stream;     /* hipStream_t for ingest, or NULL: the library creates one */
+    void*   weights_arena;   /* device, >= bz_sizes.weights_arena_bytes, 256-byte aligned; NULL: library allocates */
+    void*   kv_arena;        /* device, >= bz_sizes.kv_arena_bytes; NULL: library allocates */
+    void*   workspace;       /* device, >= bz_sizes.workspace_bytes; NULL: library allocates */
+    size_t  weights_arena_bytes;
+    size_t  kv_arena_bytes;
+    size_t  workspace_bytes;
+} bz_config;
+
+typedef struct bz_sizes {
+    size_t layer_bytes;          /* exact size of one layer blob */
+    size_t layer_stride;         /* distance between layers in the weight arena (256-byte multiple) */
+    size_t weights_arena_bytes;
+    size_t kv_arena_bytes;
+    size_t workspace_bytes;
+    size_t act_elem_bytes;       /* 2 (bf16) or 4 (fp32 debug build) */
+} bz_sizes;
+
+/* Byte offsets of the nine tensors inside a layer blob.  Every tensor is bf16, row-major;
+ * projection matrices are [out_features, in_features].  Order in the blob:
+ *   g1[H]  wq[Hq*d,H]  wk[Hkv*d,H]  wv[Hkv*d,H]  wo[H,Hq*d]  g2[H]  wg[F,H]  wu[F,H]  wd[H,F]
+ * (wq,wk,wv are adjacent and form one [(Hq+2Hkv)*d, H] matrix; wg,wu likewise [2F, H]). */
+typedef struct bz_layer_layout {
+    size_t g1, wq, wk, wv, wo, g2, wg, wu, wd;
+    size_t total;                /* == bz_sizes.layer_bytes */
+} bz_layer_layout;
+
+/* One packed ragged batch.  Sequence s owns rows q_start[s] .. q_start[s+1]-1 of the [T,H] hidden
+ * states, lives in KV slot seq_slot[s], and already has kv_len_before[s] cached positions; its new
+ * tokens take positions kv_len_before[s] + 0, 1, ...  A sequence with exactly one new token is
+ * served by the decode-attention kernel, one with more by the prefill kernel; both may be mixed
+ * in one batch (section 5.4, PD colocation).  All three arrays are host memory, read during the
+ * call only. */
+typedef struct bz_batch_desc {
+    int32_t        n_seqs;          /* B >= 1 */
+    const int32_t* q_start;         /* [B+1], q_start[0] == 0, non-decreasing; T = q_start[B] */
+    const int32_t* seq_slot;        /* [B], distinct, each in [0, max_seqs) */
+    const int32_t* kv_len_before;   /* [B], >= 0 */
+} bz_batch_desc;
+
+typedef struct bz_stats {
+    uint64_t bytes_ingested;     /* sum of layer bytes whose copies were enqueued */
+    uint64_t layers_requested;
+    uint64_t tokens_run;         /* sum over bz_run_layers calls of T * (b - a) */
+    uint64_t layer_launches;     /* layers enqueued by bz_run_layers */
+    int32_t  frontier;
+    int32_t  reserved;
+} bz_stats;
+
+/* Kernel classes for bz_profile_read. */
+enum {
+    BZ_K_RMSNORM = 0, BZ_K_GEMM_QKV, BZ_K_ROPE_APPEND, BZ_K_ATTN_PREFILL, BZ_K_ATTN_DECODE,
+    BZ_K_ATTN_COMBINE, BZ_K_GEMM_O, BZ_K_GEMM_GATEUP, BZ_K_GEMM_DOWN, BZ_K_COUNT
+};
+typedef struct bz_profile {
+    uint64_t launches[BZ_K_COUNT];
+    double   ms[BZ_K_COUNT];        /* summed HIP-event time of those launches */
+    double   flops[BZ_K_COUNT];     /* summed algorithmic flops (2*M*N*K for GEMMs, causal half for attention) */
+    double   bytes[BZ_K_COUNT];     /* summed algorithmic HBM bytes (decode attention: K and V read once) */
+} bz_profile;
+
+/* ---- pure helpers (no GPU, no instance) ------------------------------------------------ */
+
+const char* bz_strerror(int status);
+int         bz_build_info(void);                  /* BZ_BUILD_* bits */
+const char* bz_last_hip_error(void);              /* text of the last failed HIP call on this thread */
+
+/* Validates `cfg` (shape limits above) and reports blob, arena and workspace sizes. */
+int bz_query_sizes(const bz_config* cfg, bz_sizes* out);
+int bz_layer_layout_of(const bz_config* cfg, bz_layer_layout* out);
+
+/* ---- instance ---------------------------------------------------------------------------- */
+
+/* Creates an instance: allocates (or adopts) arenas, creates streams and per-layer events, builds
+ * the rotary table (angles in float64 on the host).  This is control-plane work the paper keeps
+ * off the scaling path (appendix A.1, pre-created contexts), so it is outside any TTFT figure.
+ * Adopted arenas and streams stay owned by the caller and must outlive the instance. */
+int bz_create(const bz_config* cfg, bz_instance** out);
+int bz_destroy(bz_instance* inst);               /* waits for both streams, frees what the library allocated */
+int bz_sync(bz_instance* inst);                  /* waits for both streams */
+
+/* Layer ingest (section 4: load the next layers while loaded ones execute; section 5.1: layers
+ * arrive one by one).  Enqueues chunked async copies of `n` == layer_bytes bytes from pinned host
+ * memory `host` into layer i's slot of the weight arena on the copy stream, records the layer's
+ * event and returns at once.  `host` is borrowed until the layer is resident.  Layers may be
+ * requested in any order.  BZ_EBUSY if layer i is loading or resident. */
+int bz_load_layer(bz_instance* inst, int layer, const void* host, size_t n);
+/* Same, from a device buffer (a resident peer's copy: one hop of section 5.1's forwarding chain). */
+int bz_load_layer_from_device(bz_instance* inst, int layer, const void* dev, size_t n);
+/* Forgets layer i (waits for both streams first); it must be loaded again before it can run. */
+int bz_unload_layer(bz_instance* inst, int layer);
+
+/* Number k of leading layers [0,k) that are resident now.  Never blocks. */
+int bz_frontier(bz_instance* inst);
+/* 1 if layer i is resident, 0 if requested but still in flight or never requested.  Never blocks. */
+int bz_layer_ready(bz_instance* inst, int layer);
+/* Blocks the host until layer i is resident.  BZ_ENOTLOADED if it was never requested. */
+int bz_wait_layer(bz_instance* inst, int layer);
+/* Milliseconds from the first bz_load_layer (since creation or the last bz_reset_clock) to layer
+ * i's residency, from HIP events on the copy stream.  Layer must be resident. */
+int bz_layer_ready_ms(bz_instance* inst, int layer, float* ms);
+int bz_reset_clock(bz_instance* inst);
+/* Debug: copies layer i's device bytes to host memory `host` (layer_bytes) and waits. */
+int bz_readback_layer(bz_instance* inst, int layer, void* host);
+
+/* ---- KV slots ------------------------------------------------------------------------------ */
+
+/* Reserves room for `capacity_tokens` positions (in every layer) for slot `slot`.  BZ_ECAPACITY
+ * if the arena has no contiguous room, BZ_EBUSY if the slot is reserved already. */
+int bz_kv_reserve(bz_instance* inst, int slot, int capacity_tokens);
+int bz_kv_release(bz_instance* inst, int slot);
+int64_t bz_kv_free_tokens(bz_instance* inst);    /* largest reservable capacity right now */
+/* Writes / reads n positions starting at pos0 of (layer, slot): k and v are [n, Hkv, d] activation
+ * elements, token-major, in host (is_host != 0) or device memory.  Ordered on the compute stream;
+ * host transfers complete before return. */
+int bz_kv_write(bz_instance* inst, int layer, int slot, int pos0, int n, const void* k, const void* v, int is_host);
+int bz_kv_read(bz_instance* inst, int layer, int slot, int pos0, int n, void* k, void* v, int is_host);
+
+/* ---- batches ------------------------------------------------------------------------------- */
+
+/* Builds the device-side description of a packed batch (offsets, per-token sequence ids, attention
+ * work lists).  A batch is independent of any instance and can be run by several (the two
+ * instances of a split run share one).  The upload is synchronous. */
+int bz_batch_create(const bz_batch_desc* desc, bz_batch** out);
+int bz_batch_destroy(bz_batch* batch);
+int bz_batch_tokens(const bz_batch* batch);
+/* For a batch in which every sequence has exactly one new token: enqueue, on `inst`'s compute
+ * stream, kv_len_before[s] += 1 for all s — the next decode step of the same sequences. */
+int bz_batch_advance(bz_instance* inst, bz_batch* batch);
+
+/* ---- execution ------------------------------------------------------------------------------ */
+
+/* Runs decoder layers [a,b) in order on the compute stream over `hidden` — device, [T,H]
+ * activation elements, updated in place — appending the new tokens' K/V of those layers to the
+ * instance's cache.  Before layer i's first kernel the compute stream waits on layer i's ingest
+ * event, so the call may be issued while later layers are still arriving (section 5.2, step 2 of
+ * the protocol).  With BZ_RUN_NOWAIT it returns BZ_ENOTREADY instead if any layer of [a,b) is not
+ * resident yet.  Results do not depend on a, b, the frontier or timing: running [a,k) then [k,b)
+ * (on this or another instance holding the same weights) is bit-identical to running [a,b). */
+int bz_run_layers(bz_instance* inst, int a, int b, const bz_batch* batch, void* hidden, int flags);
+
+/* Activation hand-off at a layer boundary (section 4: the scaled instance "forwards the
+ * activation" to the other one).  Bit-preserving copy of T rows of H activation elements between
+ * `hidden` (device) and `buf` (device, or pinned/ordinary host when is_host != 0), ordered on the
+ * compute stream.  Host copies complete before return. */
+int bz_export_boundary(bz_instance* inst, const void* hidden, size_t T, void* buf, int is_host);
+int bz_import_boundary(bz_instance* inst, void* hidden, size_t T, const void* buf, int is_host);
+
+/* ---- counters -------------------------------------------------------------------------------- */
+
+int bz_stats_read(bz_instance* inst, bz_stats* out);
+/* Per-kernel-class HIP-event timing of bz_run_layers.  While enabled every kernel launch is
+ * bracketed by two events on the compute stream; bz_profile_read waits for the stream, sums the
+ * intervals recorded since the last read and clears them. */
+int bz_profile_enable(bz_instance* inst, int on);
+int bz_profile_read(bz_instance* inst, bz_profile* out);
+
+/* ---- single operations (the layer's steps, exposed for tests and micro-benchmarks) ---------- */
+/* All pointers are device memory; work is enqueued on `stream` (a hipStream_t, NULL = default).
+ * Activations are activation elements (bf16, or float in the fp32 debug build); weights bf16. */
+
+/* y[T,H] = x / sqrt(mean(x^2) + eps) * gain */
+int bz_op_rmsnorm(const void* x, const void* gain, void* y, int T, int H, float eps, void* stream);
+/* mode 0: c[M,N] = a[M,K] * w[N,K]^T
+ * mode 1: c[M,N] = r[M,N] + a * w^T          (r may alias c)
+ * mode 2: w is [2N,K] (gate rows then up rows): c[M,N] = silu(a*wg^T) .* (a*wu^T) */
+int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLITZ_LAYER_H */

@@ -141,6 +141,15 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
+def linear(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """y = x W^T for a weight stored [out_features, in_features]."""
+    return np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+
+
+def swiglu(m: np.ndarray, wg: np.ndarray, wu: np.ndarray) -> np.ndarray:
+    return silu(linear(m, wg)) * linear(m, wu)
+
+
 def layer_forward(shape: OracleShape, w: dict, layer: int, x: np.ndarray, batch: OracleBatch,
                   kv: OracleKV) -> np.ndarray:
     """One decoder layer over a packed batch.  `w` maps tensor names (g1, wq, wk, wv, wo, g2, wg,
@@ -150,9 +159,9 @@ def layer_forward(shape: OracleShape, w: dict, layer: int, x: np.ndarray, batch:
     W = {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
     T = x.shape[0]
     n = rmsnorm(x, W["g1"], s.eps)
-    q = (n @ W["wq"].T).reshape(T, s.Hq, s.d)
-    k = (n @ W["wk"].T).reshape(T, s.Hkv, s.d)
-    v = (n @ W["wv"].T).reshape(T, s.Hkv, s.d)
+    q = linear(n, W["wq"]).reshape(T, s.Hq, s.d)
+    k = linear(n, W["wk"]).reshape(T, s.Hkv, s.d)
+    v = linear(n, W["wv"]).reshape(T, s.Hkv, s.d)
     o = np.empty((T, s.Hq, s.d), dtype=np.float64)
     for b in range(batch.B):
         r0, r1 = int(batch.q_start[b]), int(batch.q_start[b + 1])
@@ -167,10 +176,9 @@ def layer_forward(shape: OracleShape, w: dict, layer: int, x: np.ndarray, batch:
         cache[0] = np.concatenate([cache[0], kb], axis=0)
         cache[1] = np.concatenate([cache[1], v[r0:r1]], axis=0)
         o[r0:r1] = attention(qb, cache[0], cache[1], pos)
-    hmid = x + o.reshape(T, s.Hq * s.d) @ W["wo"].T
+    hmid = x + linear(o.reshape(T, s.Hq * s.d), W["wo"])
     m = rmsnorm(hmid, W["g2"], s.eps)
-    act = silu(m @ W["wg"].T) * (m @ W["wu"].T)
-    return hmid + act @ W["wd"].T
+    return hmid + linear(swiglu(m, W["wg"], W["wu"]), W["wd"])
 
 
 def run_layers(shape: OracleShape, weights, a: int, b: int, x: np.ndarray, batch: OracleBatch,

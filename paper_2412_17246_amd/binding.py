@@ -1,0 +1,367 @@
+"""ctypes binding of include/blitz_layer.h: argument marshalling only.
+
+Every step of the hot path runs inside the shared library; this module loads it, mirrors its
+structs, turns negative status codes into exceptions, and uses PyTorch solely to own device
+memory, pinned host memory and HIP streams.  There is no CPU fallback: if the library is not
+built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libblitzlayer.so")
+LIB_FP32_PATH = os.path.join(_PKG, "libblitzlayer_fp32dbg.so")
+
+BZ_FLAG_DRY_RUN = 1
+BZ_RUN_NOWAIT = 1
+BZ_BUILD_FP32_DEBUG = 1
+STATUS = {0: "BZ_OK", -1: "BZ_EINVAL", -2: "BZ_ENOMEM", -3: "BZ_EBUSY", -4: "BZ_ENOTLOADED",
+          -5: "BZ_ENOTREADY", -6: "BZ_EHIP", -7: "BZ_ECAPACITY", -8: "BZ_ESTATE"}
+KERNEL_CLASSES = ("rmsnorm", "gemm_qkv", "rope_append", "attn_prefill", "attn_decode", "attn_combine",
+                  "gemm_o", "gemm_gateup", "gemm_down")
+TENSOR_ORDER = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
+
+
+class BzError(RuntimeError):
+    def __init__(self, status: int, what: str, detail: str = ""):
+        self.status = status
+        self.name = STATUS.get(status, str(status))
+        super().__init__(f"{what}: {self.name}" + (f" ({detail})" if detail else ""))
+
+
+class bz_config(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("ffn", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
+        ("max_seqs", C.c_int32), ("max_seq_len", C.c_int32), ("max_tokens", C.c_int32), ("flags", C.c_int32),
+        ("kv_tokens", C.c_int64), ("chunk_bytes", C.c_int64),
+        ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
+        ("weights_arena", C.c_void_p), ("kv_arena", C.c_void_p), ("workspace", C.c_void_p),
+        ("weights_arena_bytes", C.c_size_t), ("kv_arena_bytes", C.c_size_t), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class bz_sizes(C.Structure):
+    _fields_ = [("layer_bytes", C.c_size_t), ("layer_stride", C.c_size_t), ("weights_arena_bytes", C.c_size_t),
+                ("kv_arena_bytes", C.c_size_t), ("workspace_bytes", C.c_size_t), ("act_elem_bytes", C.c_size_t)]
+
+
+class bz_layer_layout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in TENSOR_ORDER] + [("total", C.c_size_t)]
+
+
+class bz_batch_desc(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32), ("q_start", C.POINTER(C.c_int32)), ("seq_slot", C.POINTER(C.c_int32)),
+                ("kv_len_before", C.POINTER(C.c_int32))]
+
+
+class bz_stats(C.Structure):
+    _fields_ = [("bytes_ingested", C.c_uint64), ("layers_requested", C.c_uint64), ("tokens_run", C.c_uint64),
+                ("layer_launches", C.c_uint64), ("frontier", C.c_int32), ("reserved", C.c_int32)]
+
+
+_NK = len(KERNEL_CLASSES)
+
+
+class bz_profile(C.Structure):
+    _fields_ = [("launches", C.c_uint64 * _NK), ("ms", C.c_double * _NK), ("flops", C.c_double * _NK),
+                ("bytes", C.c_double * _NK)]
+
+
+# name -> (restype, argtypes); also the list of symbols the header declares
+_P = C.c_void_p
+SIGNATURES = {
+    "bz_strerror": (C.c_char_p, [C.c_int]),
+    "bz_build_info": (C.c_int, []),
+    "bz_last_hip_error": (C.c_char_p, []),
+    "bz_query_sizes": (C.c_int, [C.POINTER(bz_config), C.POINTER(bz_sizes)]),
+    "bz_layer_layout_of": (C.c_int, [C.POINTER(bz_config), C.POINTER(bz_layer_layout)]),
+    "bz_create": (C.c_int, [C.POINTER(bz_config), C.POINTER(_P)]),
+    "bz_destroy": (C.c_int, [_P]),
+    "bz_sync": (C.c_int, [_P]),
+    "bz_load_layer": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
+    "bz_load_layer_from_device": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
+    "bz_unload_layer": (C.c_int, [_P, C.c_int]),
+    "bz_frontier": (C.c_int, [_P]),
+    "bz_layer_ready": (C.c_int, [_P, C.c_int]),
+    "bz_wait_layer": (C.c_int, [_P, C.c_int]),
+    "bz_layer_ready_ms": (C.c_int, [_P, C.c_int, C.POINTER(C.c_float)]),
+    "bz_reset_clock": (C.c_int, [_P]),
+    "bz_readback_layer": (C.c_int, [_P, C.c_int, _P]),
+    "bz_kv_reserve": (C.c_int, [_P, C.c_int, C.c_int]),
+    "bz_kv_release": (C.c_int, [_P, C.c_int]),
+    "bz_kv_free_tokens": (C.c_int64, [_P]),
+    "bz_kv_write": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, C.c_int]),
+    "bz_kv_read": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, C.c_int]),
+    "bz_batch_create": (C.c_int, [C.POINTER(bz_batch_desc), C.POINTER(_P)]),
+    "bz_batch_destroy": (C.c_int, [_P]),
+    "bz_batch_tokens": (C.c_int, [_P]),
+    "bz_batch_advance": (C.c_int, [_P, _P]),
+    "bz_run_layers": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, C.c_int]),
+    "bz_export_boundary": (C.c_int, [_P, _P, C.c_size_t, _P, C.c_int]),
+    "bz_import_boundary": (C.c_int, [_P, _P, C.c_size_t, _P, C.c_int]),
+    "bz_stats_read": (C.c_int, [_P, C.POINTER(bz_stats)]),
+    "bz_profile_enable": (C.c_int, [_P, C.c_int]),
+    "bz_profile_read": (C.c_int, [_P, C.POINTER(bz_profile)]),
+    "bz_op_rmsnorm": (C.c_int, [_P, _P, _P, C.c_int, C.c_int, C.c_float, _P]),
+    "bz_op_gemm": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]),
+}
+
+_libs: Dict[str, C.CDLL] = {}
+
+
+def load_library(fp32_debug: bool = False) -> C.CDLL:
+    path = LIB_FP32_PATH if fp32_debug else LIB_PATH
+    if path in _libs:
+        return _libs[path]
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built: run `python -m paper_2412_17246_amd.build` "
+                           "(there is no fallback path)")
+    lib = C.CDLL(path)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _libs[path] = lib
+    return lib
+
+
+def make_config(shape, *, max_seqs: int, max_seq_len: int, max_tokens: int, kv_tokens: int,
+                chunk_bytes: int = 0, flags: int = 0) -> bz_config:
+    """`shape` is any object with L, H, Hq, Hkv, d, F, eps, rope_base attributes."""
+    c = bz_config()
+    c.n_layers, c.hidden, c.n_q_heads, c.n_kv_heads = shape.L, shape.H, shape.Hq, shape.Hkv
+    c.head_dim, c.ffn, c.rms_eps, c.rope_base = shape.d, shape.F, shape.eps, shape.rope_base
+    c.max_seqs, c.max_seq_len, c.max_tokens, c.flags = max_seqs, max_seq_len, max_tokens, flags
+    c.kv_tokens, c.chunk_bytes = kv_tokens, chunk_bytes
+    return c
+
+
+def _ptr(x) -> int:
+    """Address of a torch tensor, numpy array or raw integer."""
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    return x.data_ptr()
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class Batch:
+    def __init__(self, lib: C.CDLL, q_start: Sequence[int], seq_slot: Sequence[int], kv_len_before: Sequence[int]):
+        self._lib = lib
+        qs, sl, kb = _i32(q_start), _i32(seq_slot), _i32(kv_len_before)
+        if qs.size != sl.size + 1 or kb.size != sl.size:
+            raise ValueError("q_start must have one more entry than seq_slot / kv_len_before")
+        d = bz_batch_desc(int(sl.size), qs.ctypes.data_as(C.POINTER(C.c_int32)), sl.ctypes.data_as(C.POINTER(C.c_int32)),
+                          kb.ctypes.data_as(C.POINTER(C.c_int32)))
+        h = _P()
+        rc = lib.bz_batch_create(C.byref(d), C.byref(h))
+        if rc:
+            raise BzError(rc, "bz_batch_create", lib.bz_last_hip_error().decode())
+        self.handle = h
+        self.T = int(qs[-1])
+        self.B = int(sl.size)
+
+    def close(self):
+        if self.handle:
+            self._lib.bz_batch_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Instance:
+    """One serving instance on the current GPU.  Arenas are torch tensors, streams are torch streams."""
+
+    def __init__(self, shape, *, max_seqs: int, max_seq_len: int, max_tokens: int, kv_tokens: int,
+                 chunk_bytes: int = 0, fp32_debug: bool = False, dry_run: bool = False,
+                 compute_stream=None, copy_stream=None, device: str = "cuda:0"):
+        self.lib = load_library(fp32_debug)
+        self.shape = shape
+        self.fp32_debug = fp32_debug
+        cfg = make_config(shape, max_seqs=max_seqs, max_seq_len=max_seq_len, max_tokens=max_tokens,
+                          kv_tokens=kv_tokens, chunk_bytes=chunk_bytes, flags=BZ_FLAG_DRY_RUN if dry_run else 0)
+        self.sizes = bz_sizes()
+        self._check(self.lib.bz_query_sizes(C.byref(cfg), C.byref(self.sizes)), "bz_query_sizes")
+        self.layout = bz_layer_layout()
+        self._check(self.lib.bz_layer_layout_of(C.byref(cfg), C.byref(self.layout)), "bz_layer_layout_of")
+        self.dry_run = dry_run
+        self._keep = []
+        if not dry_run:
+            import torch
+            self.torch = torch
+            self.device = torch.device(device)
+            self.compute_stream = compute_stream or torch.cuda.Stream(device=self.device)
+            self.copy_stream = copy_stream or torch.cuda.Stream(device=self.device)
+            self.weights_arena = torch.empty(self.sizes.weights_arena_bytes, dtype=torch.uint8, device=self.device)
+            self.kv_arena = torch.zeros(self.sizes.kv_arena_bytes, dtype=torch.uint8, device=self.device)
+            self.workspace = torch.empty(self.sizes.workspace_bytes, dtype=torch.uint8, device=self.device)
+            cfg.compute_stream = self.compute_stream.cuda_stream
+            cfg.copy_stream = self.copy_stream.cuda_stream
+            cfg.weights_arena, cfg.weights_arena_bytes = self.weights_arena.data_ptr(), self.weights_arena.numel()
+            cfg.kv_arena, cfg.kv_arena_bytes = self.kv_arena.data_ptr(), self.kv_arena.numel()
+            cfg.workspace, cfg.workspace_bytes = self.workspace.data_ptr(), self.workspace.numel()
+            torch.cuda.synchronize(self.device)
+        self.cfg = cfg
+        h = _P()
+        self._check(self.lib.bz_create(C.byref(cfg), C.byref(h)), "bz_create")
+        self.handle = h
+
+    # -- helpers
+    def _check(self, rc: int, what: str) -> int:
+        if rc < 0:
+            raise BzError(rc, what, self.lib.bz_last_hip_error().decode() if rc == -6 else "")
+        return rc
+
+    @property
+    def layer_bytes(self) -> int:
+        return int(self.sizes.layer_bytes)
+
+    @property
+    def act_dtype(self):
+        return self.torch.float32 if self.fp32_debug else self.torch.bfloat16
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.lib.bz_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- layer blobs
+    def pack_layer(self, tensors: Dict[str, np.ndarray]) -> np.ndarray:
+        """Lays the nine tensors (uint16 bf16 bit patterns) out as one layer blob (uint8)."""
+        blob = np.empty(self.layer_bytes, dtype=np.uint8)
+        for name in TENSOR_ORDER:
+            t = np.ascontiguousarray(tensors[name], dtype=np.uint16).reshape(-1).view(np.uint8)
+            off = getattr(self.layout, name)
+            blob[off:off + t.size] = t
+        return blob
+
+    def pinned_blob(self, blob: np.ndarray):
+        """Copies a blob into a new pinned host tensor."""
+        t = self.torch.empty(blob.size, dtype=self.torch.uint8, pin_memory=True)
+        t.numpy()[:] = blob
+        return t
+
+    # -- ingest
+    def load_layer(self, layer: int, pinned) -> None:
+        self._keep.append(pinned)
+        self._check(self.lib.bz_load_layer(self.handle, layer, _ptr(pinned), pinned.numel()), "bz_load_layer")
+
+    def load_layer_from_device(self, layer: int, dev) -> None:
+        self._keep.append(dev)
+        self._check(self.lib.bz_load_layer_from_device(self.handle, layer, _ptr(dev), dev.numel()),
+                    "bz_load_layer_from_device")
+
+    def unload_layer(self, layer: int) -> None:
+        self._check(self.lib.bz_unload_layer(self.handle, layer), "bz_unload_layer")
+
+    def frontier(self) -> int:
+        return self._check(self.lib.bz_frontier(self.handle), "bz_frontier")
+
+    def layer_ready(self, layer: int) -> bool:
+        return bool(self._check(self.lib.bz_layer_ready(self.handle, layer), "bz_layer_ready"))
+
+    def wait_layer(self, layer: int) -> None:
+        self._check(self.lib.bz_wait_layer(self.handle, layer), "bz_wait_layer")
+
+    def layer_ready_ms(self, layer: int) -> float:
+        v = C.c_float()
+        self._check(self.lib.bz_layer_ready_ms(self.handle, layer, C.byref(v)), "bz_layer_ready_ms")
+        return float(v.value)
+
+    def reset_clock(self) -> None:
+        self._check(self.lib.bz_reset_clock(self.handle), "bz_reset_clock")
+
+    def readback_layer(self, layer: int) -> np.ndarray:
+        out = np.empty(self.layer_bytes, dtype=np.uint8)
+        self._check(self.lib.bz_readback_layer(self.handle, layer, out.ctypes.data), "bz_readback_layer")
+        return out
+
+    def sync(self) -> None:
+        self._check(self.lib.bz_sync(self.handle), "bz_sync")
+
+    # -- KV
+    def kv_reserve(self, slot: int, capacity: int) -> None:
+        self._check(self.lib.bz_kv_reserve(self.handle, slot, capacity), "bz_kv_reserve")
+
+    def kv_release(self, slot: int) -> None:
+        self._check(self.lib.bz_kv_release(self.handle, slot), "bz_kv_release")
+
+    def kv_free_tokens(self) -> int:
+        return int(self._check(self.lib.bz_kv_free_tokens(self.handle), "bz_kv_free_tokens"))
+
+    def kv_write(self, layer: int, slot: int, pos0: int, n: int, k, v) -> None:
+        is_host = int(isinstance(k, np.ndarray))
+        self._check(self.lib.bz_kv_write(self.handle, layer, slot, pos0, n, _ptr(k), _ptr(v), is_host), "bz_kv_write")
+
+    def kv_read(self, layer: int, slot: int, pos0: int, n: int, k, v) -> None:
+        is_host = int(isinstance(k, np.ndarray))
+        self._check(self.lib.bz_kv_read(self.handle, layer, slot, pos0, n, _ptr(k), _ptr(v), is_host), "bz_kv_read")
+
+    # -- batches and execution
+    def batch(self, q_start, seq_slot, kv_len_before) -> Batch:
+        return Batch(self.lib, q_start, seq_slot, kv_len_before)
+
+    def batch_advance(self, batch: Batch) -> None:
+        self._check(self.lib.bz_batch_advance(self.handle, batch.handle), "bz_batch_advance")
+
+    def run_layers(self, a: int, b: int, batch: Batch, hidden, flags: int = 0) -> None:
+        self._check(self.lib.bz_run_layers(self.handle, a, b, batch.handle, _ptr(hidden), flags), "bz_run_layers")
+
+    def export_boundary(self, hidden, T: int, buf) -> None:
+        is_host = int(isinstance(buf, np.ndarray) or (hasattr(buf, "is_cuda") and not buf.is_cuda))
+        self._check(self.lib.bz_export_boundary(self.handle, _ptr(hidden), T, _ptr(buf), is_host), "bz_export_boundary")
+
+    def import_boundary(self, hidden, T: int, buf) -> None:
+        is_host = int(isinstance(buf, np.ndarray) or (hasattr(buf, "is_cuda") and not buf.is_cuda))
+        self._check(self.lib.bz_import_boundary(self.handle, _ptr(hidden), T, _ptr(buf), is_host), "bz_import_boundary")
+
+    # -- counters
+    def stats(self) -> dict:
+        s = bz_stats()
+        self._check(self.lib.bz_stats_read(self.handle, C.byref(s)), "bz_stats_read")
+        return {n: int(getattr(s, n)) for n, _ in bz_stats._fields_ if n != "reserved"}
+
+    def profile_enable(self, on: bool) -> None:
+        self._check(self.lib.bz_profile_enable(self.handle, int(on)), "bz_profile_enable")
+
+    def profile_read(self) -> dict:
+        p = bz_profile()
+        self._check(self.lib.bz_profile_read(self.handle, C.byref(p)), "bz_profile_read")
+        return {name: {"launches": int(p.launches[i]), "ms": float(p.ms[i]), "flops": float(p.flops[i]),
+                       "bytes": float(p.bytes[i])} for i, name in enumerate(KERNEL_CLASSES)}
+
+
+def op_rmsnorm(x, gain, y, eps: float, stream=None, fp32_debug: bool = False) -> None:
+    lib = load_library(fp32_debug)
+    rc = lib.bz_op_rmsnorm(_ptr(x), _ptr(gain), _ptr(y), x.shape[0], x.shape[1], eps, stream.cuda_stream if stream else 0)
+    if rc:
+        raise BzError(rc, "bz_op_rmsnorm")
+
+
+def op_gemm(mode: int, a, w, r, c, M: int, N: int, K: int, stream=None, fp32_debug: bool = False) -> None:
+    lib = load_library(fp32_debug)
+    rc = lib.bz_op_gemm(mode, _ptr(a), _ptr(w), _ptr(r), _ptr(c), M, N, K, stream.cuda_stream if stream else 0)
+    if rc:
+        raise BzError(rc, "bz_op_gemm")

@@ -1,0 +1,110 @@
+// Internal definitions shared by the library's host code and kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "blitz_layer.h"
+
+namespace bz {
+
+typedef __bf16 bf16;
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Activation element: bf16 in the product build, float in the fp32 debug build.
+#ifdef BZ_FP32_DEBUG
+typedef float act_t;
+#else
+typedef bf16 act_t;
+#endif
+
+constexpr int kWave = 64;
+
+// ---- 8-element loads / stores, converting to and from float --------------------------------
+__device__ __forceinline__ void load8(const bf16* p, float (&v)[8]) {
+    bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (float)t[i];
+}
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+    float4 a = reinterpret_cast<const float4*>(p)[0];
+    float4 b = reinterpret_cast<const float4*>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
+    bf16x8 t;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = (bf16)v[i];
+    *reinterpret_cast<bf16x8*>(p) = t;
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+    reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ void from_f32(bf16& o, float v) { o = (bf16)v; }
+__device__ __forceinline__ void from_f32(float& o, float v) { o = v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+// Device-side view of the KV cache of one layer.  K part then V part; inside a part, slot s
+// starts at element slot_off[s] * Hkv * d and is laid out [Hkv][slot_cap[s]][d].
+struct KvView {
+    act_t* k;                 // layer's K part
+    act_t* v;                 // layer's V part
+    const int32_t* slot_off;  // [max_seqs] first token of the slot inside the arena
+    const int32_t* slot_cap;  // [max_seqs] capacity in tokens
+    int Hkv;
+    int d;
+};
+
+// Device-side view of a batch.
+struct BatchView {
+    int B;
+    int T;
+    const int32_t* q_start;     // [B+1]
+    const int32_t* seq_slot;    // [B]
+    const int32_t* kv_before;   // [B]
+    const int32_t* token_seq;   // [T] sequence index of each packed row
+    const int32_t* prefill_items;  // [n_prefill_items][2] = (seq, q_tile)
+    int n_prefill_items;
+    const int32_t* decode_seqs;    // [n_decode] sequence indices with exactly one new token
+    int n_decode;
+    int decode_chunks;             // upper bound on ceil((kv_before+1)/kDecodeChunk) over decode seqs
+};
+
+constexpr int kPrefillTileQ = 128;   // query rows per prefill-attention workgroup
+constexpr int kDecodeChunk = 256;    // KV positions per decode-attention workgroup
+
+// ---- launchers (each enqueues on `st`; shapes are validated by the callers) ------------------
+void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, float eps, hipStream_t st);
+void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
+                 hipStream_t st);
+void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, const KvView& kv, int Hq,
+                        hipStream_t st);
+void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,
+                         hipStream_t st);
+void launch_attn_decode(const act_t* qkv, act_t* out, float* partial, const BatchView& bv, const KvView& kv,
+                        int Hq, hipStream_t st_);
+void launch_kv_scatter(const act_t* src_k, const act_t* src_v, const KvView& kv, int slot, int pos0, int n,
+                       bool to_cache, act_t* dst_k, act_t* dst_v, hipStream_t st);
+void launch_batch_advance(int32_t* kv_before, int B, hipStream_t st);
+
+// floats per (decode sequence, query head, chunk) in the decode partial buffer: d outputs, max, sum
+__host__ __device__ inline int decode_partial_stride(int d) { return d + 2; }
+
+}  // namespace bz

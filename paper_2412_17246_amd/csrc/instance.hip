@@ -1,0 +1,778 @@
+// Host side of the C ABI: instance state, layer ingest with per-layer events, the frontier,
+// KV slots, batches, the per-layer kernel sequence, boundary hand-off, counters.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "kv_slots.h"
+
+using namespace bz;
+
+namespace {
+
+thread_local std::string g_hip_err;
+
+int hip_fail(hipError_t e, const char* what) {
+    char buf[256];
+    snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+    g_hip_err = buf;
+    return BZ_EHIP;
+}
+#define HIP_TRY(call)                                   \
+    do {                                                \
+        hipError_t e__ = (call);                        \
+        if (e__ != hipSuccess) return hip_fail(e__, #call); \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Shape {
+    int L, H, Hq, Hkv, d, F;
+    int nqkv() const { return (Hq + 2 * Hkv) * d; }
+};
+
+int validate(const bz_config* c) {
+    if (!c) return BZ_EINVAL;
+    if (c->n_layers < 1 || c->hidden < 8 || c->hidden % 8) return BZ_EINVAL;
+    if (c->head_dim != 64 && c->head_dim != 128) return BZ_EINVAL;
+    if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return BZ_EINVAL;
+    const int g = c->n_q_heads / c->n_kv_heads;
+    if (g != 1 && g != 2 && g != 4 && g != 8) return BZ_EINVAL;
+    if (c->ffn < 8 || c->ffn % 8) return BZ_EINVAL;
+    if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return BZ_EINVAL;
+    if (c->max_seqs < 1 || c->max_seq_len < 1 || c->max_tokens < 1) return BZ_EINVAL;
+#ifdef BZ_FP32_DEBUG
+    if (c->max_seq_len > 16384) return BZ_EINVAL;       // the debug attention keeps a row of scores in LDS
+#endif
+    if (c->kv_tokens < 1 || c->kv_tokens > 0x7fffffffLL) return BZ_EINVAL;
+    if (c->chunk_bytes < 0) return BZ_EINVAL;
+    return BZ_OK;
+}
+
+void layout_of(const bz_config* c, bz_layer_layout* o) {
+    const size_t H = c->hidden, d = c->head_dim, Hq = c->n_q_heads, Hkv = c->n_kv_heads, F = c->ffn;
+    size_t p = 0;
+    o->g1 = p; p += H * 2;
+    o->wq = p; p += Hq * d * H * 2;
+    o->wk = p; p += Hkv * d * H * 2;
+    o->wv = p; p += Hkv * d * H * 2;
+    o->wo = p; p += H * Hq * d * 2;
+    o->g2 = p; p += H * 2;
+    o->wg = p; p += F * H * 2;
+    o->wu = p; p += F * H * 2;
+    o->wd = p; p += H * F * 2;
+    o->total = p;
+}
+
+struct WsLayout {
+    size_t normed, qkv, attn, act, partial, rope, slot_off, slot_cap, total;
+};
+
+void ws_layout(const bz_config* c, WsLayout* w) {
+    const size_t T = c->max_tokens, e = sizeof(act_t);
+    const size_t nqkv = (size_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+    size_t p = 0;
+    auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes, 256); return at; };
+    w->normed = take(T * c->hidden * e);
+    w->qkv = take(T * nqkv * e);
+    w->attn = take(T * (size_t)c->n_q_heads * c->head_dim * e);
+    w->act = take(T * c->ffn * e);
+    const size_t chunks = (c->max_seq_len + kDecodeChunk - 1) / kDecodeChunk;
+    w->partial = take((size_t)c->max_seqs * c->n_q_heads * chunks * decode_partial_stride(c->head_dim) * sizeof(float));
+    w->rope = take((size_t)c->max_seq_len * c->head_dim * sizeof(float));
+    w->slot_off = take((size_t)c->max_seqs * sizeof(int32_t));
+    w->slot_cap = take((size_t)c->max_seqs * sizeof(int32_t));
+    w->total = p;
+}
+
+enum LayerState { kNone = 0, kLoading = 1, kResident = 2 };
+
+struct ProfRec {
+    int cls;
+    hipEvent_t e0, e1;
+    double flops, bytes;
+};
+
+}  // namespace
+
+struct bz_batch {
+    int B = 0, T = 0;
+    bool all_decode = false;
+    std::vector<int32_t> q_start, seq_slot, kv_before;
+    int n_prefill_items = 0, n_decode = 0;
+    std::vector<int32_t> decode_seqs;
+    double prefill_sq = 0;            // sum over prefill sequences of visible (query, key) pairs
+    void* dev = nullptr;              // one allocation holding all device arrays
+    int32_t *d_q_start = nullptr, *d_seq_slot = nullptr, *d_kv_before = nullptr, *d_token_seq = nullptr,
+            *d_items = nullptr, *d_decode = nullptr;
+};
+
+struct bz_instance {
+    bz_config cfg;
+    Shape sh;
+    bz_sizes sz;
+    bz_layer_layout lay;
+    WsLayout ws;
+    bool dry = false;
+    hipStream_t compute = nullptr, copy = nullptr;
+    bool own_compute = false, own_copy = false;
+    unsigned char* weights = nullptr;
+    unsigned char* kv = nullptr;
+    unsigned char* wsp = nullptr;
+    bool own_weights = false, own_kv = false, own_ws = false;
+    std::vector<int> state;
+    std::vector<hipEvent_t> ev;
+    hipEvent_t t0 = nullptr;
+    bool clock_started = false;
+    KvSlots* slots = nullptr;
+    bz_stats stats;
+    bool prof_on = false;
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> ev_pool;
+};
+
+namespace {
+
+unsigned char* layer_ptr(bz_instance* I, int l) { return I->weights + (size_t)l * I->sz.layer_stride; }
+
+KvView kv_view(bz_instance* I, int layer) {
+    const size_t part = (size_t)I->cfg.kv_tokens * I->sh.Hkv * I->sh.d;     // elements in a K or V part
+    act_t* base = reinterpret_cast<act_t*>(I->kv) + (size_t)layer * 2 * part;
+    KvView v;
+    v.k = base;
+    v.v = base + part;
+    v.slot_off = reinterpret_cast<const int32_t*>(I->wsp + I->ws.slot_off);
+    v.slot_cap = reinterpret_cast<const int32_t*>(I->wsp + I->ws.slot_cap);
+    v.Hkv = I->sh.Hkv;
+    v.d = I->sh.d;
+    return v;
+}
+
+BatchView batch_view(const bz_batch* b) {
+    BatchView v;
+    v.B = b->B;
+    v.T = b->T;
+    v.q_start = b->d_q_start;
+    v.seq_slot = b->d_seq_slot;
+    v.kv_before = b->d_kv_before;
+    v.token_seq = b->d_token_seq;
+    v.prefill_items = b->d_items;
+    v.n_prefill_items = b->n_prefill_items;
+    v.decode_seqs = b->d_decode;
+    v.n_decode = b->n_decode;
+    int mx = 0;
+    for (int s : b->decode_seqs) mx = mx > b->kv_before[s] + 1 ? mx : b->kv_before[s] + 1;
+    v.decode_chunks = (mx + kDecodeChunk - 1) / kDecodeChunk;
+    return v;
+}
+
+int poll_layer(bz_instance* I, int l) {
+    if (I->state[l] == kLoading) {
+        hipError_t e = hipEventQuery(I->ev[l]);
+        if (e == hipSuccess) I->state[l] = kResident;
+        else if (e != hipErrorNotReady) return hip_fail(e, "hipEventQuery");
+    }
+    return BZ_OK;
+}
+
+hipEvent_t take_event(bz_instance* I) {
+    if (!I->ev_pool.empty()) {
+        hipEvent_t e = I->ev_pool.back();
+        I->ev_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct ProfScope {
+    bz_instance* I;
+    ProfRec rec;
+    bool on;
+    ProfScope(bz_instance* inst, int cls, double flops, double bytes) : I(inst), on(inst->prof_on) {
+        if (!on) return;
+        rec.cls = cls;
+        rec.flops = flops;
+        rec.bytes = bytes;
+        rec.e0 = take_event(I);
+        rec.e1 = take_event(I);
+        if (!rec.e0 || !rec.e1) { on = false; return; }
+        (void)hipEventRecord(rec.e0, I->compute);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(rec.e1, I->compute);
+        I->prof.push_back(rec);
+    }
+};
+
+int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpyKind kind) {
+    if (!I || !src) return BZ_EINVAL;
+    if (layer < 0 || layer >= I->sh.L || n != I->sz.layer_bytes) return BZ_EINVAL;
+    if (I->state[layer] != kNone) return BZ_EBUSY;
+    if (I->dry) return BZ_ESTATE;
+    if (!I->clock_started) {
+        HIP_TRY(hipEventRecord(I->t0, I->copy));
+        I->clock_started = true;
+    }
+    const size_t chunk = I->cfg.chunk_bytes > 0 ? (size_t)I->cfg.chunk_bytes : ((size_t)32 << 20);
+    unsigned char* dst = layer_ptr(I, layer);
+    const unsigned char* s = static_cast<const unsigned char*>(src);
+    for (size_t off = 0; off < n; off += chunk) {
+        const size_t m = n - off < chunk ? n - off : chunk;
+        HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy));
+    }
+    HIP_TRY(hipEventRecord(I->ev[layer], I->copy));
+    I->state[layer] = kLoading;
+    I->stats.bytes_ingested += n;
+    I->stats.layers_requested += 1;
+    return BZ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bz_strerror(int st) {
+    switch (st) {
+        case BZ_OK: return "ok";
+        case BZ_EINVAL: return "invalid argument";
+        case BZ_ENOMEM: return "out of memory or arena too small";
+        case BZ_EBUSY: return "layer or slot already in use";
+        case BZ_ENOTLOADED: return "layer was never requested";
+        case BZ_ENOTREADY: return "layer not resident yet";
+        case BZ_EHIP: return "HIP runtime error";
+        case BZ_ECAPACITY: return "capacity exceeded";
+        case BZ_ESTATE: return "call not valid in this state";
+        default: return "unknown status";
+    }
+}
+
+int bz_build_info(void) {
+#ifdef BZ_FP32_DEBUG
+    return BZ_BUILD_FP32_DEBUG;
+#else
+    return 0;
+#endif
+}
+
+const char* bz_last_hip_error(void) { return g_hip_err.c_str(); }
+
+int bz_layer_layout_of(const bz_config* cfg, bz_layer_layout* out) {
+    if (!out) return BZ_EINVAL;
+    int rc = validate(cfg);
+    if (rc) return rc;
+    layout_of(cfg, out);
+    return BZ_OK;
+}
+
+int bz_query_sizes(const bz_config* cfg, bz_sizes* out) {
+    if (!out) return BZ_EINVAL;
+    int rc = validate(cfg);
+    if (rc) return rc;
+    bz_layer_layout lay;
+    layout_of(cfg, &lay);
+    WsLayout ws;
+    ws_layout(cfg, &ws);
+    out->layer_bytes = lay.total;
+    out->layer_stride = align_up(lay.total, 256);
+    out->weights_arena_bytes = out->layer_stride * (size_t)cfg->n_layers;
+    out->kv_arena_bytes = (size_t)cfg->n_layers * 2 * (size_t)cfg->kv_tokens * cfg->n_kv_heads * cfg->head_dim * sizeof(act_t);
+    out->workspace_bytes = ws.total;
+    out->act_elem_bytes = sizeof(act_t);
+    return BZ_OK;
+}
+
+int bz_destroy(bz_instance* I) {
+    if (!I) return BZ_EINVAL;
+    if (!I->dry) {
+        if (I->compute) (void)hipStreamSynchronize(I->compute);
+        if (I->copy) (void)hipStreamSynchronize(I->copy);
+        for (hipEvent_t e : I->ev) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : I->ev_pool) (void)hipEventDestroy(e);
+        for (auto& r : I->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+        if (I->t0) (void)hipEventDestroy(I->t0);
+        if (I->own_weights && I->weights) (void)hipFree(I->weights);
+        if (I->own_kv && I->kv) (void)hipFree(I->kv);
+        if (I->own_ws && I->wsp) (void)hipFree(I->wsp);
+        if (I->own_compute && I->compute) (void)hipStreamDestroy(I->compute);
+        if (I->own_copy && I->copy) (void)hipStreamDestroy(I->copy);
+    }
+    delete I->slots;
+    delete I;
+    return BZ_OK;
+}
+
+int bz_create(const bz_config* cfg, bz_instance** out) {
+    if (!out) return BZ_EINVAL;
+    *out = nullptr;
+    int rc = validate(cfg);
+    if (rc) return rc;
+    bz_instance* I = new (std::nothrow) bz_instance();
+    if (!I) return BZ_ENOMEM;
+    I->cfg = *cfg;
+    I->sh = Shape{cfg->n_layers, cfg->hidden, cfg->n_q_heads, cfg->n_kv_heads, cfg->head_dim, cfg->ffn};
+    bz_query_sizes(cfg, &I->sz);
+    layout_of(cfg, &I->lay);
+    ws_layout(cfg, &I->ws);
+    I->dry = (cfg->flags & BZ_FLAG_DRY_RUN) != 0;
+    I->state.assign(cfg->n_layers, kNone);
+    I->slots = new KvSlots(cfg->max_seqs, cfg->kv_tokens);
+    memset(&I->stats, 0, sizeof I->stats);
+    if (I->dry) {
+        *out = I;
+        return BZ_OK;
+    }
+    auto fail = [&](int code) { bz_destroy(I); return code; };
+#define HIP_TRY_C(call)                                                       \
+    do {                                                                      \
+        hipError_t e__ = (call);                                              \
+        if (e__ != hipSuccess) { hip_fail(e__, #call); return fail(BZ_EHIP); } \
+    } while (0)
+    if (cfg->compute_stream) I->compute = (hipStream_t)cfg->compute_stream;
+    else { HIP_TRY_C(hipStreamCreateWithFlags(&I->compute, hipStreamNonBlocking)); I->own_compute = true; }
+    if (cfg->copy_stream) I->copy = (hipStream_t)cfg->copy_stream;
+    else { HIP_TRY_C(hipStreamCreateWithFlags(&I->copy, hipStreamNonBlocking)); I->own_copy = true; }
+    if (cfg->weights_arena) {
+        if (cfg->weights_arena_bytes < I->sz.weights_arena_bytes || ((uintptr_t)cfg->weights_arena & 255)) return fail(BZ_ENOMEM);
+        I->weights = (unsigned char*)cfg->weights_arena;
+    } else { HIP_TRY_C(hipMalloc((void**)&I->weights, I->sz.weights_arena_bytes)); I->own_weights = true; }
+    if (cfg->kv_arena) {
+        if (cfg->kv_arena_bytes < I->sz.kv_arena_bytes || ((uintptr_t)cfg->kv_arena & 255)) return fail(BZ_ENOMEM);
+        I->kv = (unsigned char*)cfg->kv_arena;
+    } else { HIP_TRY_C(hipMalloc((void**)&I->kv, I->sz.kv_arena_bytes)); I->own_kv = true; }
+    if (cfg->workspace) {
+        if (cfg->workspace_bytes < I->sz.workspace_bytes || ((uintptr_t)cfg->workspace & 255)) return fail(BZ_ENOMEM);
+        I->wsp = (unsigned char*)cfg->workspace;
+    } else { HIP_TRY_C(hipMalloc((void**)&I->wsp, I->sz.workspace_bytes)); I->own_ws = true; }
+    I->ev.assign(cfg->n_layers, nullptr);
+    for (int l = 0; l < cfg->n_layers; ++l) HIP_TRY_C(hipEventCreate(&I->ev[l]));
+    HIP_TRY_C(hipEventCreate(&I->t0));
+    {   // rotary table: angle = pos * base^(-2j/d) in float64, stored as (cos, sin) floats
+        const int d = cfg->head_dim, half = d / 2;
+        std::vector<float> tab((size_t)cfg->max_seq_len * d);
+        std::vector<double> theta(half);
+        for (int j = 0; j < half; ++j) theta[j] = pow((double)cfg->rope_base, -2.0 * j / d);
+        for (int p = 0; p < cfg->max_seq_len; ++p)
+            for (int j = 0; j < half; ++j) {
+                const double a = (double)p * theta[j];
+                tab[((size_t)p * half + j) * 2] = (float)cos(a);
+                tab[((size_t)p * half + j) * 2 + 1] = (float)sin(a);
+            }
+        HIP_TRY_C(hipMemcpy(I->wsp + I->ws.rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice));
+    }
+    HIP_TRY_C(hipMemset(I->wsp + I->ws.slot_off, 0, (size_t)cfg->max_seqs * sizeof(int32_t)));
+    HIP_TRY_C(hipMemset(I->wsp + I->ws.slot_cap, 0, (size_t)cfg->max_seqs * sizeof(int32_t)));
+    HIP_TRY_C(hipDeviceSynchronize());
+#undef HIP_TRY_C
+    *out = I;
+    return BZ_OK;
+}
+
+int bz_sync(bz_instance* I) {
+    if (!I) return BZ_EINVAL;
+    if (I->dry) return BZ_OK;
+    HIP_TRY(hipStreamSynchronize(I->copy));
+    HIP_TRY(hipStreamSynchronize(I->compute));
+    return BZ_OK;
+}
+
+int bz_load_layer(bz_instance* I, int layer, const void* host, size_t n) {
+    return enqueue_copy(I, layer, host, n, hipMemcpyHostToDevice);
+}
+
+int bz_load_layer_from_device(bz_instance* I, int layer, const void* dev, size_t n) {
+    return enqueue_copy(I, layer, dev, n, hipMemcpyDeviceToDevice);
+}
+
+int bz_unload_layer(bz_instance* I, int layer) {
+    if (!I || layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
+    int rc = bz_sync(I);
+    if (rc) return rc;
+    I->state[layer] = kNone;
+    return BZ_OK;
+}
+
+int bz_frontier(bz_instance* I) {
+    if (!I) return BZ_EINVAL;
+    int k = 0;
+    for (; k < I->sh.L; ++k) {
+        if (I->state[k] == kNone) break;
+        if (!I->dry) {
+            int rc = poll_layer(I, k);
+            if (rc) return rc;
+        }
+        if (I->state[k] != kResident) break;
+    }
+    return k;
+}
+
+int bz_layer_ready(bz_instance* I, int layer) {
+    if (!I || layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
+    if (I->state[layer] == kNone) return 0;
+    if (!I->dry) {
+        int rc = poll_layer(I, layer);
+        if (rc) return rc;
+    }
+    return I->state[layer] == kResident ? 1 : 0;
+}
+
+int bz_wait_layer(bz_instance* I, int layer) {
+    if (!I || layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
+    if (I->state[layer] == kNone) return BZ_ENOTLOADED;
+    if (I->dry) return BZ_ESTATE;
+    HIP_TRY(hipEventSynchronize(I->ev[layer]));
+    I->state[layer] = kResident;
+    return BZ_OK;
+}
+
+int bz_layer_ready_ms(bz_instance* I, int layer, float* ms) {
+    if (!I || !ms || layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
+    if (I->dry || !I->clock_started) return BZ_ESTATE;
+    int r = bz_layer_ready(I, layer);
+    if (r < 0) return r;
+    if (r == 0) return BZ_ENOTREADY;
+    HIP_TRY(hipEventElapsedTime(ms, I->t0, I->ev[layer]));
+    return BZ_OK;
+}
+
+int bz_reset_clock(bz_instance* I) {
+    if (!I) return BZ_EINVAL;
+    I->clock_started = false;
+    return BZ_OK;
+}
+
+int bz_readback_layer(bz_instance* I, int layer, void* host) {
+    if (!I || !host || layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
+    if (I->state[layer] == kNone) return BZ_ENOTLOADED;
+    if (I->dry) return BZ_ESTATE;
+    int rc = bz_wait_layer(I, layer);
+    if (rc) return rc;
+    HIP_TRY(hipMemcpy(host, layer_ptr(I, layer), I->sz.layer_bytes, hipMemcpyDeviceToHost));
+    return BZ_OK;
+}
+
+// ---- KV slots -----------------------------------------------------------------------------
+
+static int push_slot(bz_instance* I, int slot) {
+    if (I->dry) return BZ_OK;
+    const int32_t off = I->slots->reserved(slot) ? (int32_t)I->slots->offset(slot) : 0;
+    const int32_t cap = I->slots->reserved(slot) ? (int32_t)I->slots->capacity(slot) : 0;
+    HIP_TRY(hipMemcpy(I->wsp + I->ws.slot_off + (size_t)slot * 4, &off, 4, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(I->wsp + I->ws.slot_cap + (size_t)slot * 4, &cap, 4, hipMemcpyHostToDevice));
+    return BZ_OK;
+}
+
+int bz_kv_reserve(bz_instance* I, int slot, int capacity_tokens) {
+    if (!I || slot < 0 || slot >= I->cfg.max_seqs || capacity_tokens < 1) return BZ_EINVAL;
+    if (capacity_tokens > I->cfg.max_seq_len) return BZ_ECAPACITY;
+    if (I->slots->reserved(slot)) return BZ_EBUSY;
+    if (!I->slots->reserve(slot, capacity_tokens)) return BZ_ECAPACITY;
+    return push_slot(I, slot);
+}
+
+int bz_kv_release(bz_instance* I, int slot) {
+    if (!I || slot < 0 || slot >= I->cfg.max_seqs) return BZ_EINVAL;
+    if (!I->slots->reserved(slot)) return BZ_ESTATE;
+    if (!I->dry) {
+        int rc = bz_sync(I);      // no kernel may still be reading the slot
+        if (rc) return rc;
+    }
+    I->slots->release(slot);
+    return push_slot(I, slot);
+}
+
+int64_t bz_kv_free_tokens(bz_instance* I) {
+    if (!I) return BZ_EINVAL;
+    return I->slots->largest_free();
+}
+
+static int kv_xfer(bz_instance* I, int layer, int slot, int pos0, int n, const void* k, const void* v, void* ko,
+                   void* vo, int is_host, bool to_cache) {
+    if (!I || layer < 0 || layer >= I->sh.L || slot < 0 || slot >= I->cfg.max_seqs || pos0 < 0 || n < 0) return BZ_EINVAL;
+    if (to_cache ? (!k || !v) : (!ko || !vo)) return BZ_EINVAL;
+    if (!I->slots->reserved(slot)) return BZ_ESTATE;
+    if ((int64_t)pos0 + n > I->slots->capacity(slot)) return BZ_ECAPACITY;
+    if (I->dry) return BZ_ESTATE;
+    if (n == 0) return BZ_OK;
+    const size_t bytes = (size_t)n * I->sh.Hkv * I->sh.d * sizeof(act_t);
+    const KvView view = kv_view(I, layer);
+    if (!is_host) {
+        launch_kv_scatter((const act_t*)k, (const act_t*)v, view, slot, pos0, n, to_cache, (act_t*)ko, (act_t*)vo, I->compute);
+        HIP_TRY(hipGetLastError());
+        return BZ_OK;
+    }
+    unsigned char* tmp = nullptr;
+    HIP_TRY(hipMalloc((void**)&tmp, 2 * bytes));
+    int rc = BZ_OK;
+    hipError_t e = hipSuccess;
+    if (to_cache) {
+        e = hipMemcpyAsync(tmp, k, bytes, hipMemcpyHostToDevice, I->compute);
+        if (e == hipSuccess) e = hipMemcpyAsync(tmp + bytes, v, bytes, hipMemcpyHostToDevice, I->compute);
+        if (e == hipSuccess) {
+            launch_kv_scatter((const act_t*)tmp, (const act_t*)(tmp + bytes), view, slot, pos0, n, true, nullptr, nullptr, I->compute);
+            e = hipGetLastError();
+        }
+    } else {
+        launch_kv_scatter(nullptr, nullptr, view, slot, pos0, n, false, (act_t*)tmp, (act_t*)(tmp + bytes), I->compute);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipMemcpyAsync(ko, tmp, bytes, hipMemcpyDeviceToHost, I->compute);
+        if (e == hipSuccess) e = hipMemcpyAsync(vo, tmp + bytes, bytes, hipMemcpyDeviceToHost, I->compute);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(I->compute);
+    if (e != hipSuccess) rc = hip_fail(e, "kv transfer");
+    (void)hipFree(tmp);
+    return rc;
+}
+
+int bz_kv_write(bz_instance* I, int layer, int slot, int pos0, int n, const void* k, const void* v, int is_host) {
+    return kv_xfer(I, layer, slot, pos0, n, k, v, nullptr, nullptr, is_host, true);
+}
+
+int bz_kv_read(bz_instance* I, int layer, int slot, int pos0, int n, void* k, void* v, int is_host) {
+    return kv_xfer(I, layer, slot, pos0, n, nullptr, nullptr, k, v, is_host, false);
+}
+
+// ---- batches ------------------------------------------------------------------------------
+
+int bz_batch_destroy(bz_batch* b) {
+    if (!b) return BZ_EINVAL;
+    if (b->dev) (void)hipFree(b->dev);
+    delete b;
+    return BZ_OK;
+}
+
+int bz_batch_create(const bz_batch_desc* d, bz_batch** out) {
+    if (!out) return BZ_EINVAL;
+    *out = nullptr;
+    if (!d || d->n_seqs < 1 || !d->q_start || !d->seq_slot || !d->kv_len_before) return BZ_EINVAL;
+    const int B = d->n_seqs;
+    if (d->q_start[0] != 0) return BZ_EINVAL;
+    for (int s = 0; s < B; ++s) {
+        if (d->q_start[s + 1] < d->q_start[s] || d->kv_len_before[s] < 0 || d->seq_slot[s] < 0) return BZ_EINVAL;
+        for (int u = 0; u < s; ++u)
+            if (d->seq_slot[u] == d->seq_slot[s]) return BZ_EINVAL;
+    }
+    const int T = d->q_start[B];
+    if (T < 1) return BZ_EINVAL;
+    bz_batch* b = new (std::nothrow) bz_batch();
+    if (!b) return BZ_ENOMEM;
+    b->B = B;
+    b->T = T;
+    b->q_start.assign(d->q_start, d->q_start + B + 1);
+    b->seq_slot.assign(d->seq_slot, d->seq_slot + B);
+    b->kv_before.assign(d->kv_len_before, d->kv_len_before + B);
+    std::vector<int32_t> token_seq(T), items;
+    b->all_decode = true;
+    struct Item { int s, qt; long long extent; };
+    std::vector<Item> its;
+    for (int s = 0; s < B; ++s) {
+        const int qlen = b->q_start[s + 1] - b->q_start[s];
+        for (int t = b->q_start[s]; t < b->q_start[s + 1]; ++t) token_seq[t] = s;
+        if (qlen == 1) b->decode_seqs.push_back(s);
+        if (qlen != 1) b->all_decode = false;
+        if (qlen > 1) {
+            const int tiles = (qlen + kPrefillTileQ - 1) / kPrefillTileQ;
+            for (int qt = 0; qt < tiles; ++qt) {
+                const int last = (qt * kPrefillTileQ + kPrefillTileQ < qlen ? qt * kPrefillTileQ + kPrefillTileQ : qlen);
+                its.push_back({s, qt, (long long)b->kv_before[s] + last});
+            }
+            b->prefill_sq += (double)qlen * b->kv_before[s] + 0.5 * (double)qlen * (qlen + 1);
+        }
+    }
+    // longest key range first, so the tail of the grid is made of short tiles
+    std::stable_sort(its.begin(), its.end(), [](const Item& a, const Item& c) { return a.extent > c.extent; });
+    for (const Item& it : its) { items.push_back(it.s); items.push_back(it.qt); }
+    b->n_prefill_items = (int)its.size();
+    b->n_decode = (int)b->decode_seqs.size();
+
+    const size_t n_i32 = (size_t)(B + 1) + B + B + T + items.size() + b->decode_seqs.size();
+    hipError_t e = hipMalloc(&b->dev, n_i32 * 4 + 64);
+    if (e != hipSuccess) { hip_fail(e, "hipMalloc(batch)"); delete b; return BZ_EHIP; }
+    std::vector<int32_t> host;
+    host.reserve(n_i32);
+    int32_t* base = (int32_t*)b->dev;
+    auto put = [&](const std::vector<int32_t>& v) { int32_t* at = base + host.size(); host.insert(host.end(), v.begin(), v.end()); return at; };
+    b->d_q_start = put(b->q_start);
+    b->d_seq_slot = put(b->seq_slot);
+    b->d_kv_before = put(b->kv_before);
+    b->d_token_seq = put(token_seq);
+    b->d_items = put(items);
+    b->d_decode = put(b->decode_seqs);
+    e = hipMemcpy(b->dev, host.data(), host.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { hip_fail(e, "hipMemcpy(batch)"); bz_batch_destroy(b); return BZ_EHIP; }
+    *out = b;
+    return BZ_OK;
+}
+
+int bz_batch_tokens(const bz_batch* b) { return b ? b->T : BZ_EINVAL; }
+
+int bz_batch_advance(bz_instance* I, bz_batch* b) {
+    if (!I || !b) return BZ_EINVAL;
+    if (!b->all_decode) return BZ_ESTATE;
+    if (I->dry) return BZ_ESTATE;
+    launch_batch_advance(b->d_kv_before, b->B, I->compute);
+    HIP_TRY(hipGetLastError());
+    for (auto& v : b->kv_before) v += 1;
+    return BZ_OK;
+}
+
+// ---- execution ----------------------------------------------------------------------------
+
+int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hidden, int flags) {
+    if (!I || !batch || !hidden) return BZ_EINVAL;
+    if (a < 0 || b > I->sh.L || a > b) return BZ_EINVAL;
+    if (batch->T > I->cfg.max_tokens) return BZ_ECAPACITY;
+    for (int s = 0; s < batch->B; ++s) {
+        const int slot = batch->seq_slot[s];
+        if (slot >= I->cfg.max_seqs) return BZ_EINVAL;
+        if (!I->slots->reserved(slot)) return BZ_ESTATE;
+        const int qlen = batch->q_start[s + 1] - batch->q_start[s];
+        if ((int64_t)batch->kv_before[s] + qlen > I->slots->capacity(slot)) return BZ_ECAPACITY;
+    }
+    for (int l = a; l < b; ++l)
+        if (I->state[l] == kNone) return BZ_ENOTLOADED;
+    if (I->dry) return BZ_ESTATE;
+    if (flags & BZ_RUN_NOWAIT) {
+        for (int l = a; l < b; ++l) {
+            int rc = poll_layer(I, l);
+            if (rc) return rc;
+            if (I->state[l] != kResident) return BZ_ENOTREADY;
+        }
+    }
+    const Shape& sh = I->sh;
+    const int T = batch->T;
+    const BatchView bv = batch_view(batch);
+    act_t* x = static_cast<act_t*>(hidden);
+    act_t* normed = reinterpret_cast<act_t*>(I->wsp + I->ws.normed);
+    act_t* qkv = reinterpret_cast<act_t*>(I->wsp + I->ws.qkv);
+    act_t* attn = reinterpret_cast<act_t*>(I->wsp + I->ws.attn);
+    act_t* act = reinterpret_cast<act_t*>(I->wsp + I->ws.act);
+    float* partial = reinterpret_cast<float*>(I->wsp + I->ws.partial);
+    const float* rope = reinterpret_cast<const float*>(I->wsp + I->ws.rope);
+    hipStream_t st = I->compute;
+    const double e = sizeof(act_t);
+    double decode_kv = 0;
+    for (int s : batch->decode_seqs) decode_kv += (double)(batch->kv_before[s] + 1);
+
+    for (int l = a; l < b; ++l) {
+        if (I->state[l] != kResident) HIP_TRY(hipStreamWaitEvent(st, I->ev[l], 0));
+        const unsigned char* wl = layer_ptr(I, l);
+        const bf16* g1 = (const bf16*)(wl + I->lay.g1);
+        const bf16* wqkv = (const bf16*)(wl + I->lay.wq);
+        const bf16* wo = (const bf16*)(wl + I->lay.wo);
+        const bf16* g2 = (const bf16*)(wl + I->lay.g2);
+        const bf16* wgu = (const bf16*)(wl + I->lay.wg);
+        const bf16* wd = (const bf16*)(wl + I->lay.wd);
+        const KvView kvv = kv_view(I, l);
+        const int nqkv = sh.nqkv(), qd = sh.Hq * sh.d;
+        { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
+          launch_rmsnorm(x, g1, normed, T, sh.H, I->cfg.rms_eps, st); }
+        { ProfScope p(I, BZ_K_GEMM_QKV, 2.0 * T * nqkv * sh.H, ((double)T * sh.H + (double)T * nqkv) * e + 2.0 * nqkv * sh.H);
+          launch_gemm(0, normed, wqkv, nullptr, qkv, T, nqkv, sh.H, st); }
+        { ProfScope p(I, BZ_K_ROPE_APPEND, 3.0 * T * (sh.Hq + sh.Hkv) * sh.d, (double)T * (2.0 * sh.Hq + 4.0 * sh.Hkv) * sh.d * e);
+          launch_rope_append(qkv, rope, bv, kvv, sh.Hq, st); }
+        if (bv.n_prefill_items > 0) {
+            ProfScope p(I, BZ_K_ATTN_PREFILL, 4.0 * sh.Hq * sh.d * batch->prefill_sq, 0.0);
+            launch_attn_prefill(qkv, attn, bv, kvv, sh.Hq, st);
+        }
+        if (bv.n_decode > 0) {
+            ProfScope p(I, BZ_K_ATTN_DECODE, 4.0 * sh.Hq * sh.d * decode_kv, decode_kv * 2.0 * sh.Hkv * sh.d * e);
+            launch_attn_decode(qkv, attn, partial, bv, kvv, sh.Hq, st);
+        }
+        { ProfScope p(I, BZ_K_GEMM_O, 2.0 * T * sh.H * qd, (2.0 * T * sh.H + (double)T * qd) * e + 2.0 * sh.H * qd);
+          launch_gemm(1, attn, wo, x, x, T, sh.H, qd, st); }
+        { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
+          launch_rmsnorm(x, g2, normed, T, sh.H, I->cfg.rms_eps, st); }
+        { ProfScope p(I, BZ_K_GEMM_GATEUP, 4.0 * T * sh.F * sh.H, ((double)T * sh.H + (double)T * sh.F) * e + 4.0 * sh.F * sh.H);
+          launch_gemm(2, normed, wgu, nullptr, act, T, sh.F, sh.H, st); }
+        { ProfScope p(I, BZ_K_GEMM_DOWN, 2.0 * T * sh.H * sh.F, (2.0 * T * sh.H + (double)T * sh.F) * e + 2.0 * sh.H * sh.F);
+          launch_gemm(1, act, wd, x, x, T, sh.H, sh.F, st); }
+        HIP_TRY(hipGetLastError());
+    }
+    I->stats.tokens_run += (uint64_t)T * (uint64_t)(b - a);
+    I->stats.layer_launches += (uint64_t)(b - a);
+    return BZ_OK;
+}
+
+int bz_export_boundary(bz_instance* I, const void* hidden, size_t T, void* buf, int is_host) {
+    if (!I || !hidden || !buf) return BZ_EINVAL;
+    if (T > (size_t)I->cfg.max_tokens) return BZ_ECAPACITY;
+    if (I->dry) return BZ_ESTATE;
+    const size_t bytes = T * I->sh.H * sizeof(act_t);
+    if (bytes == 0) return BZ_OK;
+    HIP_TRY(hipMemcpyAsync(buf, hidden, bytes, is_host ? hipMemcpyDeviceToHost : hipMemcpyDeviceToDevice, I->compute));
+    if (is_host) HIP_TRY(hipStreamSynchronize(I->compute));
+    return BZ_OK;
+}
+
+int bz_import_boundary(bz_instance* I, void* hidden, size_t T, const void* buf, int is_host) {
+    if (!I || !hidden || !buf) return BZ_EINVAL;
+    if (T > (size_t)I->cfg.max_tokens) return BZ_ECAPACITY;
+    if (I->dry) return BZ_ESTATE;
+    const size_t bytes = T * I->sh.H * sizeof(act_t);
+    if (bytes == 0) return BZ_OK;
+    HIP_TRY(hipMemcpyAsync(hidden, buf, bytes, is_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice, I->compute));
+    if (is_host) HIP_TRY(hipStreamSynchronize(I->compute));
+    return BZ_OK;
+}
+
+// ---- counters -----------------------------------------------------------------------------
+
+int bz_stats_read(bz_instance* I, bz_stats* out) {
+    if (!I || !out) return BZ_EINVAL;
+    I->stats.frontier = bz_frontier(I);
+    *out = I->stats;
+    return BZ_OK;
+}
+
+int bz_profile_enable(bz_instance* I, int on) {
+    if (!I) return BZ_EINVAL;
+    if (I->dry) return BZ_ESTATE;
+    I->prof_on = on != 0;
+    return BZ_OK;
+}
+
+int bz_profile_read(bz_instance* I, bz_profile* out) {
+    if (!I || !out) return BZ_EINVAL;
+    if (I->dry) return BZ_ESTATE;
+    memset(out, 0, sizeof *out);
+    HIP_TRY(hipStreamSynchronize(I->compute));
+    for (auto& r : I->prof) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, r.e0, r.e1));
+        out->launches[r.cls] += 1;
+        out->ms[r.cls] += ms;
+        out->flops[r.cls] += r.flops;
+        out->bytes[r.cls] += r.bytes;
+        I->ev_pool.push_back(r.e0);
+        I->ev_pool.push_back(r.e1);
+    }
+    I->prof.clear();
+    return BZ_OK;
+}
+
+// ---- single operations -----------------------------------------------------------------------
+
+int bz_op_rmsnorm(const void* x, const void* gain, void* y, int T, int H, float eps, void* stream) {
+    if (!x || !gain || !y || T < 0 || H < 8 || H % 8) return BZ_EINVAL;
+    launch_rmsnorm((const act_t*)x, (const bf16*)gain, (act_t*)y, T, H, eps, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return BZ_OK;
+}
+
+int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K, void* stream) {
+    if (mode < 0 || mode > 2 || !a || !w || !c || (mode == 1 && !r)) return BZ_EINVAL;
+    if (M < 0 || N < 1 || K < 8 || K % 8) return BZ_EINVAL;
+    launch_gemm(mode, (const act_t*)a, (const bf16*)w, (const act_t*)r, (act_t*)c, M, N, K, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return BZ_OK;
+}
+
+}  // extern "C"

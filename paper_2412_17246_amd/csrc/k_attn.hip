@@ -1,0 +1,421 @@
+// Causal attention over the KV cache: a tiled MFMA kernel for sequences with several new tokens
+// (prefill) and a split-KV kernel plus fixed-order combine for sequences with one (decode).
+//
+// Cache layout per (layer, slot, kv head): K[pos][d] and V[pos][d], pos-major.  Query head h reads
+// kv head h / (Hq/Hkv).  A query at absolute position p sees keys 0..p.  Scores are scaled by
+// 1/sqrt(d); softmax is evaluated in base 2 (scores pre-multiplied by log2 e).
+#include "common.h"
+
+namespace bz {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+#ifndef BZ_FP32_DEBUG
+// ---------------------------------------------------------------------------------------------
+// Prefill.  One workgroup = 128 query rows of one (sequence, head); each of its 4 waves owns 32
+// rows.  The wave computes S^T = K * Q^T with 32x32x16 MFMAs, so that a lane (and its partner
+// lane + 32) holds all scores of ONE query row: row max / sum need a single cross-lane exchange
+// and the running rescale of O^T is a per-lane scalar.  P^T feeds the second MFMA (O^T = V^T *
+// P^T) straight from registers: the accumulator layout of S^T is a permutation of the B-operand
+// layout along the contraction index, and V^T is read from LDS with the same permutation.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out,
+                                                           BatchView bv, KvView kv, int Hq, float scale_log2) {
+    constexpr int BQ = kPrefillTileQ, BK = 64;
+    constexpr int KROW = D + 8;      // padded LDS rows (elements)
+    constexpr int VROW = BK + 8;
+    constexpr int DB = D / 32;       // 32-wide blocks of the head dim
+    constexpr int KS = D / 16;       // MFMA k-steps over the head dim
+    __shared__ __attribute__((aligned(16))) bf16 Ks[BK * KROW];
+    __shared__ __attribute__((aligned(16))) bf16 Vt[D * VROW];
+
+    const int item = blockIdx.x, h = blockIdx.y;
+    const int s = bv.prefill_items[2 * item], qt = bv.prefill_items[2 * item + 1];
+    const int q0 = bv.q_start[s];
+    const int qlen = bv.q_start[s + 1] - q0;
+    const int before = bv.kv_before[s];
+    const int slot = bv.seq_slot[s];
+    const int Hkv = kv.Hkv;
+    const int cap = kv.slot_cap[slot];
+    const int kvh = h / (Hq / Hkv);
+    const size_t head_base = (size_t)kv.slot_off[slot] * Hkv * D + (size_t)kvh * cap * D;
+    const bf16* Kc = kv.k + head_base;
+    const bf16* Vc = kv.v + head_base;
+    const int nqkv = (Hq + 2 * Hkv) * D;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lq = lane & 31, lh = lane >> 5;
+    const int qi = qt * BQ + wave * 32 + lq;
+    const bool valid = qi < qlen;
+    const int qic = valid ? qi : qlen - 1;
+    const int qpos = before + qic;
+
+    bf16x8 qf[KS];
+    {
+        const bf16* qp = qkv + (size_t)(q0 + qic) * nqkv + h * D + lh * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    }
+
+    const int last_q = ((qt * BQ + BQ < qlen) ? qt * BQ + BQ : qlen) - 1;
+    const int kv_end = before + last_q + 1;                 // keys 0..kv_end-1 are visible to this tile
+    const int ntiles = (kv_end + BK - 1) / BK;
+    int wq_last = qt * BQ + wave * 32 + 31;
+    if (wq_last > qlen - 1) wq_last = qlen - 1;
+    const int wave_max_pos = before + wq_last;
+
+    f32x16 o[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[b][r] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int kbase = tile * BK;
+        __syncthreads();                                     // all waves are done with the previous tile
+        {   // K tile, row-major
+            constexpr int VPR = D / 8;                       // 16-byte vectors per row
+            constexpr int RPP = 256 / VPR;                   // rows per pass
+#pragma unroll
+            for (int p = 0; p < BK / RPP; ++p) {
+                const int row = tid / VPR + p * RPP, vec = tid % VPR;
+                int kp = kbase + row;
+                if (kp > kv_end - 1) kp = kv_end - 1;
+                *reinterpret_cast<uint4*>(&Ks[row * KROW + vec * 8]) =
+                    *reinterpret_cast<const uint4*>(Kc + (size_t)kp * D + vec * 8);
+            }
+        }
+        {   // V tile, transposed into Vt[d][kv]
+            constexpr int CH = D / 8;
+#pragma unroll
+            for (int p = 0; p < CH / 4; ++p) {
+                const int kr = tid & 63, c = (tid >> 6) + 4 * p;
+                int kp = kbase + kr;
+                if (kp > kv_end - 1) kp = kv_end - 1;
+                const bf16x8 v = *reinterpret_cast<const bf16x8*>(Vc + (size_t)kp * D + c * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * VROW + kr] = v[e];
+            }
+        }
+        __syncthreads();
+        if (kbase <= wave_max_pos) {                         // wave-uniform: tile not fully masked for this wave
+            f32x16 sacc[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(kb * 32 + lq) * KROW + ks * 16 + lh * 8]);
+                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
+                }
+            }
+            float mx = m;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kvi = kbase + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    float sc = sacc[kb][r] * scale_log2;
+                    if (kvi > qpos) sc = -INFINITY;
+                    sacc[kb][r] = sc;
+                    mx = fmaxf(mx, sc);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float alpha = exp2f(m - mx);               // m = -inf on the first tile -> 0
+            float rs = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = exp2f(sacc[kb][r] - mx);
+                    sacc[kb][r] = p;
+                    rs += p;
+                }
+            rs += __shfl_xor(rs, 32, kWave);
+            l = l * alpha + rs;
+            m = mx;
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                bf16x8 pf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[e] = (bf16)sacc[t >> 1][8 * (t & 1) + e];
+#pragma unroll
+                for (int b = 0; b < DB; ++b) {
+                    const bf16* vp = &Vt[(b * 32 + lq) * VROW + t * 16 + 4 * lh];
+                    const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vp);
+                    const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vp + 8);
+                    bf16x8 vf;
+                    vf[0] = v0[0]; vf[1] = v0[1]; vf[2] = v0[2]; vf[3] = v0[3];
+                    vf[4] = v1[0]; vf[5] = v1[1]; vf[6] = v1[2]; vf[7] = v1[3];
+                    o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[b], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    if (valid) {
+        const float inv = 1.0f / l;
+        bf16* op = out + (size_t)(q0 + qi) * Hq * D + h * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[b][r4 * 4 + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + b * 32 + 8 * r4 + 4 * lh) = w;
+            }
+    }
+}
+
+void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,
+                         hipStream_t st) {
+    if (bv.n_prefill_items <= 0) return;
+    const float scale_log2 = kLog2e / sqrtf((float)kv.d);
+    const dim3 grid(bv.n_prefill_items, Hq);
+    if (kv.d == 128) {
+        hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, dim3(256), 0, st, qkv, out, bv, kv, Hq, scale_log2);
+    } else {
+        hipLaunchKernelGGL(attn_prefill_kernel<64>, grid, dim3(256), 0, st, qkv, out, bv, kv, Hq, scale_log2);
+    }
+}
+
+#else  // BZ_FP32_DEBUG
+// ---------------------------------------------------------------------------------------------
+// fp32 debug prefill: one wave per (token, head); scores for all visible keys are kept in LDS and
+// softmax is the plain three-pass form.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void attn_naive_kernel(const float* __restrict__ qkv, float* __restrict__ out,
+                                                        BatchView bv, KvView kv, int Hq, float scale_log2) {
+    extern __shared__ float sc[];
+    const int t = blockIdx.x, h = blockIdx.y;
+    const int s = bv.token_seq[t];
+    if (bv.q_start[s + 1] - bv.q_start[s] <= 1) return;     // single-token sequences use the decode kernel
+    const int pos = bv.kv_before[s] + (t - bv.q_start[s]);
+    const int slot = bv.seq_slot[s];
+    const int D = kv.d, Hkv = kv.Hkv, cap = kv.slot_cap[slot];
+    const int kvh = h / (Hq / Hkv);
+    const size_t head_base = (size_t)kv.slot_off[slot] * Hkv * D + (size_t)kvh * cap * D;
+    const float* Kc = kv.k + head_base;
+    const float* Vc = kv.v + head_base;
+    const float* q = qkv + (size_t)t * (Hq + 2 * Hkv) * D + h * D;
+    const int lane = threadIdx.x;
+    float mx = -INFINITY;
+    for (int j = lane; j <= pos; j += 64) {
+        float a = 0.f;
+        for (int e = 0; e < D; ++e) a = fmaf(q[e], Kc[(size_t)j * D + e], a);
+        a *= scale_log2;
+        sc[j] = a;
+        mx = fmaxf(mx, a);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int j = lane; j <= pos; j += 64) {
+        const float p = exp2f(sc[j] - mx);
+        sc[j] = p;
+        sum += p;
+    }
+    sum = wave_sum(sum);
+    __syncthreads();
+    for (int e = lane; e < D; e += 64) {
+        float a = 0.f;
+        for (int j = 0; j <= pos; ++j) a = fmaf(sc[j], Vc[(size_t)j * D + e], a);
+        out[(size_t)t * Hq * D + h * D + e] = a / sum;
+    }
+}
+
+void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,
+                         hipStream_t st) {
+    if (bv.n_prefill_items <= 0) return;
+    const float scale_log2 = kLog2e / sqrtf((float)kv.d);
+    // 64 KiB of LDS holds 16384 scores: enough for every supported max_seq_len in the debug build
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_naive_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(attn_naive_kernel, dim3(bv.T, Hq), dim3(64), 65536, st, qkv, out, bv, kv, Hq, scale_log2);
+}
+#endif
+
+// ---------------------------------------------------------------------------------------------
+// Decode.  Grid (chunk, kv head, decode sequence).  A workgroup handles kDecodeChunk = 256 cached
+// positions of one kv head for all G = Hq/Hkv query heads that share it: every K and V byte is
+// read from HBM once.  Scores: one lane per position (the lane walks its K row in 16-byte steps).
+// PV: D/8 lanes per V row, so a wave reads whole rows with 16-byte loads.  Each workgroup writes
+// an unnormalised partial (o, running max, sum) per head; the combine kernel folds the chunks of
+// a sequence in increasing chunk order, so the result does not depend on scheduling.
+// ---------------------------------------------------------------------------------------------
+template <int D, int G>
+__global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restrict__ qkv, float* __restrict__ partial,
+                                                          BatchView bv, KvView kv, int Hq, float scale_log2) {
+    constexpr int CH = kDecodeChunk;
+    constexpr int LPR = D / 8;            // lanes per V row
+    constexpr int RPI = 64 / LPR;         // V rows per wave load
+    __shared__ float qs[G][D];
+    __shared__ float ps[G][CH];
+    __shared__ float red_m[4][G];
+    __shared__ float red_l[4][G];
+    __shared__ float osh[4][G][D];
+
+    const int chunk = blockIdx.x, kvh = blockIdx.y, di = blockIdx.z;
+    const int s = bv.decode_seqs[di];
+    const int len = bv.kv_before[s] + 1;
+    const int c0 = chunk * CH;
+    if (c0 >= len) return;
+    const int t = bv.q_start[s];
+    const int slot = bv.seq_slot[s];
+    const int Hkv = kv.Hkv, cap = kv.slot_cap[slot];
+    const size_t head_base = (size_t)kv.slot_off[slot] * Hkv * D + (size_t)kvh * cap * D;
+    const act_t* Kc = kv.k + head_base;
+    const act_t* Vc = kv.v + head_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    {
+        const act_t* q = qkv + (size_t)t * (Hq + 2 * Hkv) * D + (size_t)kvh * G * D;
+        for (int i = tid; i < G * D / 8; i += 256) {
+            float v[8];
+            load8(q + i * 8, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) (&qs[0][0])[i * 8 + e] = v[e];
+        }
+    }
+    __syncthreads();
+
+    const int pos = c0 + tid;
+    const bool valid = pos < len;
+    float sc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) sc[g] = 0.f;
+    if (valid) {
+        const act_t* kr = Kc + (size_t)pos * D;
+#pragma unroll
+        for (int c = 0; c < D / 8; ++c) {
+            float kk[8];
+            load8(kr + c * 8, kk);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sc[g] = fmaf(kk[e], qs[g][c * 8 + e], sc[g]);
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        sc[g] = valid ? sc[g] * scale_log2 : -INFINITY;
+        const float wm = wave_max(sc[g]);
+        if (lane == 0) red_m[wave][g] = wm;
+    }
+    __syncthreads();
+    float mx[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        mx[g] = fmaxf(fmaxf(red_m[0][g], red_m[1][g]), fmaxf(red_m[2][g], red_m[3][g]));
+        const float p = valid ? exp2f(sc[g] - mx[g]) : 0.f;
+        ps[g][tid] = p;
+        const float ws = wave_sum(p);
+        if (lane == 0) red_l[wave][g] = ws;
+    }
+    __syncthreads();
+
+    float o[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[g][e] = 0.f;
+    const int sub = lane / LPR, dv = (lane % LPR) * 8;
+#pragma unroll 4
+    for (int stp = 0; stp < 64 / RPI; ++stp) {
+        const int prow = wave * 64 + stp * RPI + sub;
+        if (c0 + prow < len) {
+            float vv[8];
+            load8(Vc + (size_t)(c0 + prow) * D + dv, vv);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float pw = ps[g][prow];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[g][e] = fmaf(pw, vv[e], o[g][e]);
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = o[g][e];
+#pragma unroll
+            for (int off = LPR; off < 64; off <<= 1) v += __shfl_xor(v, off, kWave);
+            o[g][e] = v;
+        }
+    if (lane < LPR) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) osh[wave][g][dv + e] = o[g][e];
+    }
+    __syncthreads();
+    const int PS = decode_partial_stride(D);
+    for (int i = tid; i < G * D; i += 256) {
+        const int g = i / D, dd = i - g * D;
+        const float v = ((osh[0][g][dd] + osh[1][g][dd]) + osh[2][g][dd]) + osh[3][g][dd];
+        partial[(((size_t)di * Hq + kvh * G + g) * bv.decode_chunks + chunk) * PS + dd] = v;
+    }
+    if (tid < G) {
+        const int g = tid;
+        float* pp = partial + (((size_t)di * Hq + kvh * G + g) * bv.decode_chunks + chunk) * PS;
+        pp[D] = fmaxf(fmaxf(red_m[0][g], red_m[1][g]), fmaxf(red_m[2][g], red_m[3][g]));
+        pp[D + 1] = ((red_l[0][g] + red_l[1][g]) + red_l[2][g]) + red_l[3][g];
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ partial, act_t* __restrict__ out,
+                                                         BatchView bv, int Hq) {
+    const int di = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
+    const int s = bv.decode_seqs[di];
+    const int len = bv.kv_before[s] + 1;
+    const int nch = (len + kDecodeChunk - 1) / kDecodeChunk;
+    const int PS = decode_partial_stride(D);
+    const float* base = partial + ((size_t)di * Hq + h) * bv.decode_chunks * PS;
+    float M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, base[c * PS + D]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < nch; ++c) {
+        const float w = exp2f(base[c * PS + D] - M);
+        num = fmaf(base[c * PS + dd], w, num);
+        den = fmaf(base[c * PS + D + 1], w, den);
+    }
+    act_t r;
+    from_f32(r, num / den);
+    out[(size_t)bv.q_start[s] * Hq * D + h * D + dd] = r;
+}
+
+template <int D>
+static void launch_decode_d(const act_t* qkv, act_t* out, float* partial, const BatchView& bv, const KvView& kv,
+                            int Hq, hipStream_t st) {
+    const float scale_log2 = kLog2e / sqrtf((float)D);
+    const dim3 grid(bv.decode_chunks, kv.Hkv, bv.n_decode);
+    switch (Hq / kv.Hkv) {
+        case 1: hipLaunchKernelGGL((attn_decode_kernel<D, 1>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
+        case 2: hipLaunchKernelGGL((attn_decode_kernel<D, 2>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
+        case 4: hipLaunchKernelGGL((attn_decode_kernel<D, 4>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
+        default: hipLaunchKernelGGL((attn_decode_kernel<D, 8>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
+    }
+    hipLaunchKernelGGL(attn_combine_kernel<D>, dim3(bv.n_decode, Hq), dim3(D), 0, st, partial, out, bv, Hq);
+}
+
+void launch_attn_decode(const act_t* qkv, act_t* out, float* partial, const BatchView& bv, const KvView& kv,
+                        int Hq, hipStream_t st) {
+    if (bv.n_decode <= 0) return;
+    if (kv.d == 128) launch_decode_d<128>(qkv, out, partial, bv, kv, Hq, st);
+    else launch_decode_d<64>(qkv, out, partial, bv, kv, Hq, st);
+}
+
+}  // namespace bz

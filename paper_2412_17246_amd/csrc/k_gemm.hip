@@ -1,0 +1,276 @@
+// Projections of a decoder layer: C[M,N] = A[M,K] * W[N,K]^T with bf16 inputs, fp32 accumulation on
+// the matrix cores (v_mfma_f32_32x32x16_bf16), and three epilogues: plain, + residual, SwiGLU.
+//
+// Both operands are K-contiguous, so a lane's MFMA operand (8 consecutive k of one row / column)
+// is one 16-byte LDS read.  Tiles are staged global -> registers -> LDS, double buffered, one
+// barrier per 64-wide K step; LDS rows are padded by 16 bytes so the 16-byte operand reads of 16
+// consecutive rows fall in distinct banks.
+#include "common.h"
+
+namespace bz {
+
+#ifndef BZ_FP32_DEBUG
+
+constexpr int kBK = 64;            // K step per LDS stage
+constexpr int kLdsRow = kBK + 8;   // padded row length in elements (144 bytes)
+
+template <int BM, int BN>
+constexpr int gemm_lds_bytes() { return 2 * (BM + BN) * kLdsRow * (int)sizeof(bf16); }
+
+// Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of logical tile
+// ids so tiles that share operand rows meet in one L2.
+__device__ __forceinline__ int xcd_remap(int bid, int nb) {
+    const int xcd = bid & 7, local = bid >> 3;
+    const int base = nb >> 3, rem = nb & 7;
+    return xcd * base + (xcd < rem ? xcd : rem) + local;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const bf16* __restrict__ A,
+                                                                      const bf16* __restrict__ W,
+                                                                      const bf16* R, bf16* C, int M, int N,
+                                                                      int K, int tiles_m, int tiles_n) {
+    constexpr int THREADS = WAVES_M * WAVES_N * 64;
+    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    constexpr int MI = WTM / 32, NJ = WTN / 32;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the MFMA block");
+    static_assert(MODE != 2 || NJ % 2 == 0, "SwiGLU needs gate and up blocks in the same wave");
+    constexpr int ROWS_PER_PASS = THREADS / 8;      // 8 vectors of 8 elements per 64-wide row
+    constexpr int PA = BM / ROWS_PER_PASS, PB = BN / ROWS_PER_PASS;
+    static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows vs loader passes");
+    constexpr int OUT_BN = (MODE == 2) ? BN / 2 : BN;   // output columns per tile
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* As = reinterpret_cast<bf16*>(smem_raw);                 // [2][BM][kLdsRow]
+    bf16* Bs = As + 2 * BM * kLdsRow;                             // [2][BN][kLdsRow]
+
+    // ---- tile coordinates (grouped along M for L2 reuse of the weight tile) ----
+    const int pid = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+    constexpr int GROUP = 8;
+    const int width = GROUP * tiles_n;
+    const int group_id = pid / width;
+    const int first_m = group_id * GROUP;
+    const int gsize = (tiles_m - first_m < GROUP) ? (tiles_m - first_m) : GROUP;
+    const int tile_m = first_m + (pid % width) % gsize;
+    const int tile_n = (pid % width) / gsize;
+    const int m0 = tile_m * BM;
+    const int n0 = tile_n * OUT_BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    // ---- loader mapping ----
+    const int vcol = tid & 7;             // which 8-element vector of the 64-wide row
+    const int vrow = tid >> 3;            // row within a pass
+    const bf16* a_ptr[PA];
+    const bf16* b_ptr[PB];
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+        int r = m0 + vrow + p * ROWS_PER_PASS;
+        if (r > M - 1) r = M - 1;
+        a_ptr[p] = A + (size_t)r * K + vcol * 8;
+    }
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+        const int lr = vrow + p * ROWS_PER_PASS;      // row in the LDS B tile
+        int r;
+        if (MODE == 2) {
+            const bool up = lr >= BN / 2;
+            int f = n0 + (up ? lr - BN / 2 : lr);
+            if (f > N - 1) f = N - 1;
+            r = up ? N + f : f;
+        } else {
+            r = n0 + lr;
+            if (r > N - 1) r = N - 1;
+        }
+        b_ptr[p] = W + (size_t)r * K + vcol * 8;
+    }
+
+    uint4 ra[PA], rb[PB];
+    auto load_tile = [&](int k0) {
+        const bool kin = (k0 + vcol * 8) < K;
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            ra[p] = kin ? *reinterpret_cast<const uint4*>(a_ptr[p] + k0) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+            rb[p] = kin ? *reinterpret_cast<const uint4*>(b_ptr[p] + k0) : make_uint4(0, 0, 0, 0);
+    };
+    auto store_tile = [&](int buf) {
+        bf16* as = As + buf * BM * kLdsRow;
+        bf16* bs = Bs + buf * BN * kLdsRow;
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            *reinterpret_cast<uint4*>(as + (vrow + p * ROWS_PER_PASS) * kLdsRow + vcol * 8) = ra[p];
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+            *reinterpret_cast<uint4*>(bs + (vrow + p * ROWS_PER_PASS) * kLdsRow + vcol * 8) = rb[p];
+    };
+
+    f32x16 acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // LDS row of the wave's j-th column block
+    int brow[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        if (MODE == 2) {
+            constexpr int HJ = NJ / 2 > 0 ? NJ / 2 : 1;
+            const bool up = j >= HJ;
+            const int jj = up ? j - HJ : j;
+            brow[j] = (up ? BN / 2 : 0) + (wn * HJ + jj) * 32 + lrow;
+        } else {
+            brow[j] = (wn * NJ + j) * 32 + lrow;
+        }
+    }
+
+    const int nk = (K + kBK - 1) / kBK;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_tile((kt + 1) * kBK);
+        const bf16* as = As + cur * BM * kLdsRow;
+        const bf16* bs = Bs + cur * BN * kLdsRow;
+#pragma unroll
+        for (int ks = 0; ks < kBK / 16; ++ks) {
+            bf16x8 af[MI], bfr[NJ];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[i] = *reinterpret_cast<const bf16x8*>(as + (wm * WTM + i * 32 + lrow) * kLdsRow + ks * 16 + lk * 8);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8*>(bs + brow[j] * kLdsRow + ks * 16 + lk * 8);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds column (lane%32) and rows 8*(r/4) + 4*(lane/32) + r%4 of each block
+    if (MODE == 2) {
+        constexpr int HJ = NJ / 2 > 0 ? NJ / 2 : 1;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < HJ; ++j) {
+                const int col = n0 + (wn * HJ + j) * 32 + lrow;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                    if (row < M && col < N) {
+                        const float g = acc[i][j][r], u = acc[i][j + HJ][r];
+                        const float sg = g / (1.0f + __expf(-g));
+                        C[(size_t)row * N + col] = (bf16)(sg * u);
+                    }
+                }
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int col = n0 + (wn * NJ + j) * 32 + lrow;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                    if (row < M && col < N) {
+                        float v = acc[i][j][r];
+                        if (MODE == 1) v += (float)R[(size_t)row * N + col];
+                        C[(size_t)row * N + col] = (bf16)v;
+                    }
+                }
+            }
+    }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
+static void launch_cfg(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
+    constexpr int OUT_BN = (MODE == 2) ? BN / 2 : BN;
+    constexpr int LDS = gemm_lds_bytes<BM, BN>();
+    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, MODE>;
+    static bool attr_set = false;      // one attribute per instantiation
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        attr_set = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + OUT_BN - 1) / OUT_BN;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), LDS, st, a, w, r, c, M, N, K,
+                       tiles_m, tiles_n);
+}
+
+template <int MODE>
+static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
+    // The tile shape is a function of the problem shape only, so a layer's result never depends on
+    // which range of layers a call covers.
+    if (M <= 64) {
+        launch_cfg<64, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
+    } else {
+        launch_cfg<128, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
+    }
+}
+
+void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
+                 hipStream_t st) {
+    if (M <= 0 || N <= 0) return;
+    switch (mode) {
+        case 0: launch_mode<0>(a, w, r, c, M, N, K, st); break;
+        case 1: launch_mode<1>(a, w, r, c, M, N, K, st); break;
+        default: launch_mode<2>(a, w, r, c, M, N, K, st); break;
+    }
+}
+
+#else  // BZ_FP32_DEBUG: one thread per output element, fp32 FMA chain in k order
+
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_naive_kernel(const float* __restrict__ A, const bf16* __restrict__ W,
+                                                         const float* R, float* C, int M, int N, int K) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)M * N) return;
+    const int m = (int)(idx / N), n = (int)(idx % N);
+    const float* a = A + (size_t)m * K;
+    if (MODE == 2) {
+        const bf16* wg = W + (size_t)n * K;
+        const bf16* wu = W + (size_t)(N + n) * K;
+        float g = 0.f, u = 0.f;
+        for (int k = 0; k < K; ++k) {
+            g = fmaf(a[k], (float)wg[k], g);
+            u = fmaf(a[k], (float)wu[k], u);
+        }
+        C[idx] = g / (1.0f + expf(-g)) * u;
+    } else {
+        const bf16* w = W + (size_t)n * K;
+        float s = 0.f;
+        for (int k = 0; k < K; ++k) s = fmaf(a[k], (float)w[k], s);
+        if (MODE == 1) s += R[idx];
+        C[idx] = s;
+    }
+}
+
+void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
+                 hipStream_t st) {
+    if (M <= 0 || N <= 0) return;
+    const size_t total = (size_t)M * N;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    switch (mode) {
+        case 0: hipLaunchKernelGGL(gemm_naive_kernel<0>, grid, dim3(256), 0, st, a, w, r, c, M, N, K); break;
+        case 1: hipLaunchKernelGGL(gemm_naive_kernel<1>, grid, dim3(256), 0, st, a, w, r, c, M, N, K); break;
+        default: hipLaunchKernelGGL(gemm_naive_kernel<2>, grid, dim3(256), 0, st, a, w, r, c, M, N, K); break;
+    }
+}
+
+#endif
+
+}  // namespace bz

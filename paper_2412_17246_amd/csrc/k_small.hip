@@ -1,0 +1,170 @@
+// HBM-bound steps of a decoder layer: RMSNorm, rotary embedding + KV-cache append, KV scatter /
+// gather for cache import/export, and the decode-batch position bump.
+#include "common.h"
+
+namespace bz {
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm: one workgroup per token row.  Sum of squares in fp32 (wave shuffle reduction, then a
+// fixed-order sum over the waves), y = (x * rstd) * gain rounded once to the activation type.
+// ---------------------------------------------------------------------------------------------
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void rmsnorm_kernel(const act_t* __restrict__ x,
+                                                          const bf16* __restrict__ gain,
+                                                          act_t* __restrict__ y, int H, float eps) {
+    constexpr int NW = THREADS / kWave;
+    __shared__ float red[NW];
+    const int row = blockIdx.x;
+    const act_t* xr = x + (size_t)row * H;
+    act_t* yr = y + (size_t)row * H;
+    const int nvec = H >> 3;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < nvec; i += THREADS) {
+        float v[8];
+        load8(xr + i * 8, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) tot += red[w];
+    const float rstd = 1.0f / sqrtf(tot / (float)H + eps);
+    for (int i = threadIdx.x; i < nvec; i += THREADS) {
+        float v[8], g[8];
+        load8(xr + i * 8, v);
+        load8(gain + i * 8, g);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (v[e] * rstd) * g[e];
+        store8(yr + i * 8, v);
+    }
+}
+
+void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, float eps, hipStream_t st) {
+    if (T <= 0) return;
+    if (H >= 2048) {
+        hipLaunchKernelGGL(rmsnorm_kernel<256>, dim3(T), dim3(256), 0, st, x, gain, y, H, eps);
+    } else {
+        hipLaunchKernelGGL(rmsnorm_kernel<64>, dim3(T), dim3(64), 0, st, x, gain, y, H, eps);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rotary embedding + KV append.  One workgroup per token.  Q is rotated in place inside the
+// packed [T, (Hq+2Hkv)*d] projection output; K is rotated and written to the cache; V is copied
+// to the cache.  Pairs are (j, j + d/2); the cos/sin table is [max_seq_len][d/2][2] floats built
+// on the host in float64.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qkv,
+                                                          const float* __restrict__ tab, BatchView bv,
+                                                          KvView kv, int Hq) {
+    const int t = blockIdx.x;
+    const int s = bv.token_seq[t];
+    const int pos = bv.kv_before[s] + (t - bv.q_start[s]);
+    const int slot = bv.seq_slot[s];
+    const int d = kv.d, Hkv = kv.Hkv, half = d >> 1;
+    const int cap = kv.slot_cap[slot];
+    const size_t slot_base = (size_t)kv.slot_off[slot] * Hkv * d;
+    const int nqkv = (Hq + 2 * Hkv) * d;
+    act_t* row = qkv + (size_t)t * nqkv;
+    const float* cs = tab + (size_t)pos * d;   // [half][2]
+    const int units_per_head = half >> 3;      // 8 pairs per unit
+    const int rot_units = (Hq + Hkv) * units_per_head;
+    const int v_units = Hkv * (d >> 3);
+    for (int u = threadIdx.x; u < rot_units + v_units; u += blockDim.x) {
+        if (u < rot_units) {
+            const int head = u / units_per_head;          // 0..Hq-1 query heads, then key heads
+            const int j0 = (u - head * units_per_head) * 8;
+            act_t* hp = row + head * d;
+            float lo[8], hi[8], o_lo[8], o_hi[8];
+            load8(hp + j0, lo);
+            load8(hp + half + j0, hi);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float c = cs[(j0 + e) * 2], sn = cs[(j0 + e) * 2 + 1];
+                o_lo[e] = lo[e] * c - hi[e] * sn;
+                o_hi[e] = hi[e] * c + lo[e] * sn;
+            }
+            if (head < Hq) {
+                store8(hp + j0, o_lo);
+                store8(hp + half + j0, o_hi);
+            } else {
+                const int kvh = head - Hq;
+                act_t* dst = kv.k + slot_base + ((size_t)kvh * cap + pos) * d;
+                store8(dst + j0, o_lo);
+                store8(dst + half + j0, o_hi);
+            }
+        } else {
+            const int w = u - rot_units;
+            const int kvh = w / (d >> 3);
+            const int j0 = (w - kvh * (d >> 3)) * 8;
+            float v[8];
+            load8(row + (Hq + Hkv + kvh) * d + j0, v);
+            store8(kv.v + slot_base + ((size_t)kvh * cap + pos) * d + j0, v);
+        }
+    }
+}
+
+void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, const KvView& kv, int Hq,
+                        hipStream_t st) {
+    if (bv.T <= 0) return;
+    hipLaunchKernelGGL(rope_append_kernel, dim3(bv.T), dim3(256), 0, st, qkv, rope_tab, bv, kv, Hq);
+}
+
+// ---------------------------------------------------------------------------------------------
+// KV scatter/gather between token-major [n, Hkv, d] buffers and the cache layout of one slot.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void kv_scatter_kernel(const act_t* __restrict__ src_k,
+                                                         const act_t* __restrict__ src_v, KvView kv, int slot,
+                                                         int pos0, int n, int to_cache,
+                                                         act_t* __restrict__ dst_k, act_t* __restrict__ dst_v) {
+    const int d = kv.d, Hkv = kv.Hkv;
+    const int cap = kv.slot_cap[slot];
+    const size_t slot_base = (size_t)kv.slot_off[slot] * Hkv * d;
+    const int vec_per_tok = Hkv * (d >> 3);
+    const size_t total = (size_t)n * vec_per_tok;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int tok = (int)(i / vec_per_tok);
+        const int w = (int)(i - (size_t)tok * vec_per_tok);
+        const int kvh = w / (d >> 3);
+        const int j0 = (w - kvh * (d >> 3)) * 8;
+        const size_t lin = (size_t)tok * Hkv * d + (size_t)kvh * d + j0;
+        const size_t cac = slot_base + ((size_t)kvh * cap + pos0 + tok) * d + j0;
+        float a[8], b[8];
+        if (to_cache) {
+            load8(src_k + lin, a);
+            load8(src_v + lin, b);
+            store8(kv.k + cac, a);
+            store8(kv.v + cac, b);
+        } else {
+            load8(kv.k + cac, a);
+            load8(kv.v + cac, b);
+            store8(dst_k + lin, a);
+            store8(dst_v + lin, b);
+        }
+    }
+}
+
+void launch_kv_scatter(const act_t* src_k, const act_t* src_v, const KvView& kv, int slot, int pos0, int n,
+                       bool to_cache, act_t* dst_k, act_t* dst_v, hipStream_t st) {
+    if (n <= 0) return;
+    const size_t total = (size_t)n * kv.Hkv * (kv.d >> 3);
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(kv_scatter_kernel, dim3(blocks), dim3(256), 0, st, src_k, src_v, kv, slot, pos0, n,
+                       to_cache ? 1 : 0, dst_k, dst_v);
+}
+
+__global__ void batch_advance_kernel(int32_t* kv_before, int B) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B) kv_before[i] += 1;
+}
+
+void launch_batch_advance(int32_t* kv_before, int B, hipStream_t st) {
+    hipLaunchKernelGGL(batch_advance_kernel, dim3((B + 255) / 256), dim3(256), 0, st, kv_before, B);
+}
+
+}  // namespace bz

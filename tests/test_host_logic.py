@@ -1,0 +1,152 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host-side
+logic (shape validation, blob layout, arena sizing, KV slot bookkeeping, argument checks of a
+dry-run instance) behaves as the header says.  No kernel runs here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads
+from paper_2412_17246_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", params=[False, True], ids=["bf16", "fp32dbg"])
+def lib(request):
+    return B.load_library(fp32_debug=request.param)
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    text = open(os.path.join(ROOT, "include", "blitz_layer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(bz_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    assert declared == set(B.SIGNATURES), declared ^ set(B.SIGNATURES)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_build_info_distinguishes_the_two_builds():
+    assert B.load_library(False).bz_build_info() == 0
+    assert B.load_library(True).bz_build_info() == B.BZ_BUILD_FP32_DEBUG
+
+
+@pytest.mark.parametrize("name", list(workloads.CONFIGS))
+def test_layout_and_sizes_match_the_parameter_count(lib, name):
+    s = workloads.CONFIGS[name]
+    cfg = B.make_config(s, max_seqs=4, max_seq_len=512, max_tokens=128, kv_tokens=1024)
+    sz, lay = B.bz_sizes(), B.bz_layer_layout()
+    assert lib.bz_query_sizes(C.byref(cfg), C.byref(sz)) == 0
+    assert lib.bz_layer_layout_of(C.byref(cfg), C.byref(lay)) == 0
+    assert sz.layer_bytes == 2 * s.params_per_layer == lay.total
+    assert sz.layer_stride % 256 == 0 and sz.layer_stride >= sz.layer_bytes
+    assert sz.weights_arena_bytes == sz.layer_stride * s.L
+    act = 4 if lib.bz_build_info() & 1 else 2
+    assert sz.act_elem_bytes == act
+    assert sz.kv_arena_bytes == s.L * 2 * 1024 * s.Hkv * s.d * act
+    shapes = workloads.tensor_shapes(s)
+    off = 0
+    for t in workloads.TENSOR_ORDER:
+        assert getattr(lay, t) == off and off % 16 == 0
+        off += 2 * int(np.prod(shapes[t]))
+    assert off == lay.total
+
+
+def test_paper_size_table_values(lib):
+    # bytes per layer of the five shapes (2 bytes x parameters)
+    want = {"tiny": 1_582_080, "7b": 404_766_720, "8b_gqa": 436_224_000, "13b": 634_408_960, "70b": 1_711_308_800}
+    for name, nbytes in want.items():
+        cfg = B.make_config(workloads.CONFIGS[name], max_seqs=1, max_seq_len=16, max_tokens=16, kv_tokens=16)
+        sz = B.bz_sizes()
+        assert lib.bz_query_sizes(C.byref(cfg), C.byref(sz)) == 0
+        assert sz.layer_bytes == nbytes
+
+
+@pytest.mark.parametrize("field,value", [("n_layers", 0), ("hidden", 100), ("head_dim", 96), ("n_kv_heads", 3),
+                                         ("ffn", 13), ("max_seqs", 0), ("kv_tokens", 0), ("rms_eps", 0.0),
+                                         ("n_q_heads", 48)])
+def test_bad_configs_are_rejected(lib, field, value):
+    cfg = B.make_config(workloads.CONFIGS["tiny"], max_seqs=4, max_seq_len=512, max_tokens=128, kv_tokens=1024)
+    if field == "n_q_heads":
+        cfg.n_kv_heads = 3       # 48/3 = 16 query heads per kv head: unsupported group size
+    setattr(cfg, field, value)
+    sz = B.bz_sizes()
+    assert lib.bz_query_sizes(C.byref(cfg), C.byref(sz)) == -1
+    h = C.c_void_p()
+    assert lib.bz_create(C.byref(cfg), C.byref(h)) == -1 and not h.value
+
+
+def test_strerror(lib):
+    assert lib.bz_strerror(0) == b"ok"
+    assert lib.bz_strerror(-5) == b"layer not resident yet"
+    assert lib.bz_strerror(-99) == b"unknown status"
+
+
+@pytest.fixture()
+def dry(lib):
+    inst = B.Instance(workloads.CONFIGS["tiny"], max_seqs=4, max_seq_len=100, max_tokens=64, kv_tokens=256,
+                      dry_run=True, fp32_debug=bool(lib.bz_build_info() & 1))
+    yield inst
+    inst.close()
+
+
+def _status(fn, *a):
+    try:
+        fn(*a)
+    except B.BzError as e:
+        return e.name
+    return "BZ_OK"
+
+
+def test_kv_slot_bookkeeping(dry):
+    assert dry.kv_free_tokens() == 256
+    dry.kv_reserve(0, 100)
+    dry.kv_reserve(1, 100)
+    assert _status(dry.kv_reserve, 1, 10) == "BZ_EBUSY"
+    assert _status(dry.kv_reserve, 2, 101) == "BZ_ECAPACITY"     # above max_seq_len
+    assert _status(dry.kv_reserve, 2, 57) == "BZ_ECAPACITY"      # 56 tokens left
+    assert dry.kv_free_tokens() == 56
+    dry.kv_release(0)
+    assert dry.kv_free_tokens() == 100                           # two runs: 100 and 56, not adjacent
+    dry.kv_reserve(2, 56)
+    dry.kv_release(1)
+    assert dry.kv_free_tokens() == 200                           # runs 0..100 and 100..200 merged
+    dry.kv_release(2)
+    assert dry.kv_free_tokens() == 256
+    assert _status(dry.kv_release, 2) == "BZ_ESTATE"
+    assert _status(dry.kv_reserve, 4, 10) == "BZ_EINVAL"
+
+
+def test_frontier_and_argument_checks_without_a_gpu(dry):
+    assert dry.frontier() == 0
+    assert dry.layer_ready(0) is False
+    assert _status(dry.wait_layer, 0) == "BZ_ENOTLOADED"
+    assert _status(dry.wait_layer, 2) == "BZ_EINVAL"
+    buf = np.zeros(dry.layer_bytes, dtype=np.uint8)
+    lib, h = dry.lib, dry.handle
+    assert lib.bz_load_layer(h, 0, buf.ctypes.data, buf.size - 1) == -1        # wrong size
+    assert lib.bz_load_layer(h, 5, buf.ctypes.data, buf.size) == -1            # out of range
+    assert lib.bz_load_layer(h, 0, None, buf.size) == -1
+    assert lib.bz_load_layer(h, 0, buf.ctypes.data, buf.size) == -8            # dry run: validated, not enqueued
+    assert lib.bz_readback_layer(h, 0, buf.ctypes.data) == -4
+    assert lib.bz_export_boundary(h, 1, 65, 1, 0) == -7                        # T above max_tokens
+    st = dry.stats()
+    assert st["bytes_ingested"] == 0 and st["frontier"] == 0
+
+
+def test_batch_descriptor_validation(lib):
+    def make(q, s, k):
+        q, s, k = (np.asarray(v, dtype=np.int32) for v in (q, s, k))
+        d = B.bz_batch_desc(len(s), q.ctypes.data_as(C.POINTER(C.c_int32)), s.ctypes.data_as(C.POINTER(C.c_int32)),
+                            k.ctypes.data_as(C.POINTER(C.c_int32)))
+        h = C.c_void_p()
+        return lib.bz_batch_create(C.byref(d), C.byref(h)), h
+    assert make([1, 4], [0], [0])[0] == -1          # q_start[0] != 0
+    assert make([0, 4, 2], [0, 1], [0, 0])[0] == -1  # decreasing offsets
+    assert make([0, 2, 4], [1, 1], [0, 0])[0] == -1  # duplicate slot
+    assert make([0, 2], [0], [-1])[0] == -1         # negative cache length
+    assert make([0, 0], [0], [0])[0] == -1          # no tokens at all
+    assert lib.bz_batch_create(None, C.byref(C.c_void_p())) == -1
