@@ -196,6 +196,242 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const bf16*
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Large-tile kernel for prefill-sized problems (K a multiple of 64, N a multiple of 4):
+// 256x256x64 workgroup tile, 4 waves, 128x128 per wave (256 accumulator registers), two 64 KiB LDS
+// stages filled by direct global->LDS loads (16 bytes per lane, no register staging).  A wave's
+// load instruction writes 1 KiB of LDS in lane order, i.e. 8 rows of 128 bytes; bank conflicts are
+// avoided by permuting WHICH 16-byte piece of its row each lane fetches (an XOR swizzle applied on
+// the global side) and reading operands with the same permutation.  The weight tile feeds the
+// MFMA's row operand and the activation tile its column operand, so a lane ends up with 4
+// consecutive output features of one token: 8-byte stores, and gate/up of the same feature in
+// the same lane for the SwiGLU epilogue.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBigStage = (256 + 256) * kBK * (int)sizeof(bf16);    // 65536
+
+__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void gemm_big_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
+                                                           const bf16* R, bf16* C, int M, int N, int K,
+                                                           int tiles_m, int tiles_n) {
+    constexpr int OUT_BN = (MODE == 2) ? 128 : 256;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+
+    const int pid = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+    constexpr int GROUP = 4;
+    const int width = GROUP * tiles_n;
+    const int group_id = pid / width;
+    const int first_m = group_id * GROUP;
+    const int gsize = (tiles_m - first_m < GROUP) ? (tiles_m - first_m) : GROUP;
+    const int tile_m = first_m + (pid % width) % gsize;
+    const int tile_n = (pid % width) / gsize;
+    const int m0 = tile_m * 256;
+    const int n0 = tile_n * OUT_BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    // ---- loader: this wave fills chunks q = wave*8 + j (rows 8q .. 8q+7) of both tiles.  Addresses
+    // are a uniform base (advanced per K tile) plus a per-lane 32-bit byte offset.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint32_t a_off[8], b_off[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int row = (wave * 8 + j) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ swz(row);
+        int ar = m0 + row;
+        if (ar > M - 1) ar = M - 1;
+        a_off[j] = ((uint32_t)ar * (uint32_t)K + c * 8) * 2u;
+        int br;
+        if (MODE == 2) {
+            const bool up = row >= 128;
+            int f = n0 + (up ? row - 128 : row);
+            if (f > N - 1) f = N - 1;
+            br = up ? N + f : f;
+        } else {
+            br = n0 + row;
+            if (br > N - 1) br = N - 1;
+        }
+        b_off[j] = ((uint32_t)br * (uint32_t)K + c * 8) * 2u;
+    }
+    auto issue = [&](int kt, int stage) {
+        const char* ak = reinterpret_cast<const char*>(A + (size_t)kt * kBK);
+        const char* wk = reinterpret_cast<const char*>(W + (size_t)kt * kBK);
+        unsigned char* sa = smem_raw + stage * kBigStage + wave_u * 8 * 1024;
+        unsigned char* sb = sa + 32768;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(ak + a_off[j]), (lptr_t)(sa + j * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wk + b_off[j]), (lptr_t)(sb + j * 1024), 16, 0, 0);
+        }
+    };
+
+    f32x16 acc[4][4];      // [n block][m block]
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+    // ---- operand addresses inside a stage
+    int x_off[4], w_off[4], k_off[4];
+    const int sw = swz(lrow);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x_off[i] = (wm * 128 + i * 32 + lrow) * 128;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int row;
+        if (MODE == 2) row = (j < 2) ? wn * 64 + j * 32 + lrow : 128 + wn * 64 + (j - 2) * 32 + lrow;
+        else row = wn * 128 + j * 32 + lrow;
+        w_off[j] = 32768 + row * 128;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) k_off[ks] = ((ks * 2 + lk) ^ sw) * 16;
+
+    // ---- main loop.  Operands of the next k-step are fetched from LDS while the 16 MFMAs of the
+    // current one run; the tile barrier sits before the last k-step, whose operands are already in
+    // registers, so the first operands of the next tile are fetched under those MFMAs as well.
+    bf16x8 xf[2][4], wf[2][4];
+    auto fetch = [&](const unsigned char* st, int ks, int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xf[buf][i] = *reinterpret_cast<const bf16x8*>(st + x_off[i] + k_off[ks]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8*>(st + w_off[j] + k_off[ks]);
+    };
+    auto mma = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
+    };
+    auto interleave = [&]() {       // 8 x (2 MFMA, 1 LDS read) inside the current scheduling region
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
+    auto interleave_with_loads = [&]() {   // 8 x (MFMA, LDS read, global->LDS load, MFMA, global->LDS load)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+    };
+    auto three_steps = [&](const unsigned char* st) {
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(st, 1, 1);
+        mma(0);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(st, 2, 0);
+        mma(1);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(st, 3, 1);
+        mma(0);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    const int nk = K / kBK;
+    if (M > 0x7fffffff / K || 2 * N > 0x7fffffff / K) return;    // 32-bit offsets (checked on the host too)
+    issue(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
+    __syncthreads();
+    if (nk > 1) issue(1, 1);
+    fetch(smem_raw, 0, 0);
+    for (int kt = 0; kt < nk - 2; ++kt) {             // tiles that still have a tile kt+2 to request
+        three_steps(smem_raw + (kt & 1) * kBigStage);
+        __builtin_amdgcn_s_waitcnt(0x0070);           // vmcnt(0) lgkmcnt(0): tile kt+1 landed, own reads of tile kt done
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        issue(kt + 2, kt & 1);
+        fetch(smem_raw + ((kt + 1) & 1) * kBigStage, 0, 0);
+        mma(1);
+        interleave_with_loads();
+    }
+    if (nk > 1) {                                     // tile nk-2: nothing left to request
+        three_steps(smem_raw + ((nk - 2) & 1) * kBigStage);
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(smem_raw + ((nk - 1) & 1) * kBigStage, 0, 0);
+        mma(1);
+        interleave();
+    }
+    three_steps(smem_raw + ((nk - 1) & 1) * kBigStage);
+    mma(1);
+
+    // ---- epilogue: lane holds token (lane%32) and features 8*g + 4*(lane/32) + 0..3 of each block
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + lrow;
+        if (m >= M) continue;
+        bf16* crow = C + (size_t)m * N;
+        if (MODE == 2) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * lk;
+                    if (n < N) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float gt = acc[j][i][4 * g + e], up = acc[j + 2][i][4 * g + e];
+                            o[e] = (bf16)(gt / (1.0f + __expf(-gt)) * up);
+                        }
+                        *reinterpret_cast<bf16x4*>(crow + n) = o;
+                    }
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * 128 + j * 32 + 8 * g + 4 * lk;
+                    if (n < N) {
+                        bf16x4 o;
+                        if (MODE == 1) {
+                            const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[j][i][4 * g + e] + (float)rv[e]);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[j][i][4 * g + e];
+                        }
+                        *reinterpret_cast<bf16x4*>(crow + n) = o;
+                    }
+                }
+        }
+    }
+}
+
+template <int MODE>
+static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
+    constexpr int OUT_BN = (MODE == 2) ? 128 : 256;
+    constexpr int LDS = 2 * kBigStage;
+    auto kern = gemm_big_kernel<MODE>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        attr_set = true;
+    }
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + OUT_BN - 1) / OUT_BN;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), LDS, st, a, w, r, c, M, N, K, tiles_m, tiles_n);
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
 static void launch_cfg(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
     constexpr int OUT_BN = (MODE == 2) ? BN / 2 : BN;
@@ -217,6 +453,8 @@ static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, in
     // which range of layers a call covers.
     if (M <= 64) {
         launch_cfg<64, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
+    } else if (M > 256 && K % kBK == 0 && N % 4 == 0) {
+        launch_big<MODE>(a, w, r, c, M, N, K, st);
     } else {
         launch_cfg<128, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
     }

@@ -44,6 +44,8 @@ GEMM_SHAPES = [
     # M, N, K: single tile, ragged M, ragged N (not a multiple of 32), K tail (688 = 10*64 + 48)
     (64, 128, 64), (1, 768, 256), (65, 768, 256), (200, 688, 256), (333, 256, 688), (130, 1376, 2048),
     (257, 4096, 512), (31, 48, 72),
+    # large-tile kernel (M > 256, K a multiple of 64): ragged M, N tails, one and many K tiles
+    (300, 768, 256), (700, 688, 1024), (513, 520, 64), (1030, 1024, 2048), (257, 132, 128),
 ]
 
 
