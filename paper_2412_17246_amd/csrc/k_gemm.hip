@@ -214,11 +214,22 @@ __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-template <int MODE>
-__global__ __launch_bounds__(256, 1) void gemm_big_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
-                                                           const bf16* R, bf16* C, int M, int N, int K,
-                                                           int tiles_m, int tiles_n) {
+#ifndef BZ_BIG_WN
+#define BZ_BIG_WN 2
+#endif
+
+// WN = waves along the output-feature dimension: 2 (4 waves, 128x128 per wave) or 4 (8 waves, two per
+// SIMD, 128x64 per wave).
+template <int MODE, int WN>
+__global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
+                                                                const bf16* R, bf16* C, int M, int N, int K,
+                                                                int tiles_m, int tiles_n) {
     constexpr int OUT_BN = (MODE == 2) ? 128 : 256;
+    constexpr int NWAVES = 2 * WN;
+    constexpr int NJ = 8 / WN;                 // 32-wide feature blocks per wave (gate+up blocks in SwiGLU mode)
+    constexpr int NCH = 32 / NWAVES;           // 1 KiB chunks of each tile filled by one wave
+    constexpr int NMMA = 4 * NJ;               // MFMAs per k-step
+    constexpr int NFETCH = 4 + NJ;             // LDS operand reads per k-step
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
 
     const int pid = xcd_remap(blockIdx.x, tiles_m * tiles_n);
@@ -233,16 +244,16 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(const bf16* __restrict
     const int n0 = tile_n * OUT_BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane & 31, lk = lane >> 5;
 
-    // ---- loader: this wave fills chunks q = wave*8 + j (rows 8q .. 8q+7) of both tiles.  Addresses
+    // ---- loader: this wave fills chunks q = wave*NCH + j (rows 8q .. 8q+7) of both tiles.  Addresses
     // are a uniform base (advanced per K tile) plus a per-lane 32-bit byte offset.
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    uint32_t a_off[8], b_off[8];
+    uint32_t a_off[NCH], b_off[NCH];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int row = (wave * 8 + j) * 8 + (lane >> 3);
+    for (int j = 0; j < NCH; ++j) {
+        const int row = (wave * NCH + j) * 8 + (lane >> 3);
         const int c = (lane & 7) ^ swz(row);
         int ar = m0 + row;
         if (ar > M - 1) ar = M - 1;
@@ -259,89 +270,73 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(const bf16* __restrict
         }
         b_off[j] = ((uint32_t)br * (uint32_t)K + c * 8) * 2u;
     }
-    auto issue = [&](int kt, int stage) {
-        const char* ak = reinterpret_cast<const char*>(A + (size_t)kt * kBK);
-        const char* wk = reinterpret_cast<const char*>(W + (size_t)kt * kBK);
-        unsigned char* sa = smem_raw + stage * kBigStage + wave_u * 8 * 1024;
-        unsigned char* sb = sa + 32768;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
+    auto issue_piece = [&](int kt, int stage, int q) {     // q in [0, 2*NCH): A chunks at even q, W chunks at odd q
+        const int j = q >> 1;
+        unsigned char* sa = smem_raw + stage * kBigStage + wave_u * NCH * 1024;
+        if ((q & 1) == 0) {
+            const char* ak = reinterpret_cast<const char*>(A + (size_t)kt * kBK);
             __builtin_amdgcn_global_load_lds((gptr_t)(ak + a_off[j]), (lptr_t)(sa + j * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(wk + b_off[j]), (lptr_t)(sb + j * 1024), 16, 0, 0);
+        } else {
+            const char* wk = reinterpret_cast<const char*>(W + (size_t)kt * kBK);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wk + b_off[j]), (lptr_t)(sa + 32768 + j * 1024), 16, 0, 0);
         }
     };
-
-    f32x16 acc[4][4];      // [n block][m block]
+    auto issue = [&](int kt, int stage) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+        for (int q = 0; q < 2 * NCH; ++q) issue_piece(kt, stage, q);
+    };
+
+    f32x16 acc[NJ][4];      // [feature block][token block]
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
     // ---- operand addresses inside a stage
-    int x_off[4], w_off[4], k_off[4];
+    int x_off[4], w_off[NJ], k_off[4], fbase[NJ];
     const int sw = swz(lrow);
 #pragma unroll
     for (int i = 0; i < 4; ++i) x_off[i] = (wm * 128 + i * 32 + lrow) * 128;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int row;
-        if (MODE == 2) row = (j < 2) ? wn * 64 + j * 32 + lrow : 128 + wn * 64 + (j - 2) * 32 + lrow;
-        else row = wn * 128 + j * 32 + lrow;
-        w_off[j] = 32768 + row * 128;
+    for (int j = 0; j < NJ; ++j) {
+        int row;       // row of the weight tile (0..127 gate / plain, 128..255 up / plain)
+        if (MODE == 2) row = (j < NJ / 2) ? (wn * (NJ / 2) + j) * 32 : 128 + (wn * (NJ / 2) + (j - NJ / 2)) * 32;
+        else row = (wn * NJ + j) * 32;
+        fbase[j] = (MODE == 2 && j >= NJ / 2) ? row - 128 : row;     // output feature offset inside the tile
+        w_off[j] = 32768 + (row + lrow) * 128;
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) k_off[ks] = ((ks * 2 + lk) ^ sw) * 16;
 
-    // ---- main loop.  Operands of the next k-step are fetched from LDS while the 16 MFMAs of the
-    // current one run; the tile barrier sits before the last k-step, whose operands are already in
-    // registers, so the first operands of the next tile are fetched under those MFMAs as well.
-    bf16x8 xf[2][4], wf[2][4];
+    // ---- main loop.  Every k-step is NMMA MFMAs in a fixed order; between them, one by one, go the
+    // LDS reads that fetch the operands of the NEXT k-step and (in the last k-step of a tile) the
+    // global->LDS loads of the tile after next.  The order is pinned with scheduling barriers so
+    // the matrix pipe never waits behind a burst of memory instructions.  The tile barrier sits
+    // before the last k-step, whose operands are already in registers.
+    bf16x8 xf[2][4], wf[2][NJ];
+    auto fetch_piece = [&](const unsigned char* st, int ks, int buf, int q) {   // order of first use
+        if (q == 0) wf[buf][0] = *reinterpret_cast<const bf16x8*>(st + w_off[0] + k_off[ks]);
+        else if (q <= 4) xf[buf][q - 1] = *reinterpret_cast<const bf16x8*>(st + x_off[q - 1] + k_off[ks]);
+        else wf[buf][q - 4] = *reinterpret_cast<const bf16x8*>(st + w_off[q - 4] + k_off[ks]);
+    };
     auto fetch = [&](const unsigned char* st, int ks, int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xf[buf][i] = *reinterpret_cast<const bf16x8*>(st + x_off[i] + k_off[ks]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8*>(st + w_off[j] + k_off[ks]);
+        for (int q = 0; q < NFETCH; ++q) fetch_piece(st, ks, buf, q);
     };
-    auto mma = [&](int buf) {
+    // one k-step: MFMAs from buffer `cur`; optionally fetch k-step `nks` of stage `fst` into the
+    // other buffer and request tile `ikt` into stage `istage`
+    auto kstep = [&](int cur, bool do_fetch, const unsigned char* fst, int nks, bool do_issue, int ikt, int istage) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
-    };
-    auto interleave = [&]() {       // 8 x (2 MFMA, 1 LDS read) inside the current scheduling region
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int q = 0; q < NMMA; ++q) {
+            const int j = q >> 2, i = q & 3;
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[j][i], 0, 0, 0);
+            if (do_fetch && q < NFETCH) fetch_piece(fst, nks, cur ^ 1, q);
+            if (do_issue && q < 2 * NCH) issue_piece(ikt, istage, q);
+            __builtin_amdgcn_sched_barrier(0);
         }
-    };
-    auto interleave_with_loads = [&]() {   // 8 x (MFMA, LDS read, global->LDS load, MFMA, global->LDS load)
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-    };
-    auto three_steps = [&](const unsigned char* st) {
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(st, 1, 1);
-        mma(0);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(st, 2, 0);
-        mma(1);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(st, 3, 1);
-        mma(0);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
     };
 
     const int nk = K / kBK;
@@ -352,26 +347,34 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(const bf16* __restrict
     if (nk > 1) issue(1, 1);
     fetch(smem_raw, 0, 0);
     for (int kt = 0; kt < nk - 2; ++kt) {             // tiles that still have a tile kt+2 to request
-        three_steps(smem_raw + (kt & 1) * kBigStage);
+        const unsigned char* st = smem_raw + (kt & 1) * kBigStage;
+        kstep(0, true, st, 1, false, 0, 0);
+        kstep(1, true, st, 2, false, 0, 0);
+        kstep(0, true, st, 3, false, 0, 0);
         __builtin_amdgcn_s_waitcnt(0x0070);           // vmcnt(0) lgkmcnt(0): tile kt+1 landed, own reads of tile kt done
         __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        issue(kt + 2, kt & 1);
-        fetch(smem_raw + ((kt + 1) & 1) * kBigStage, 0, 0);
-        mma(1);
-        interleave_with_loads();
+#ifdef BZ_EXP_NOLOAD
+        kstep(1, true, smem_raw + ((kt + 1) & 1) * kBigStage, 0, false, kt + 2, kt & 1);
+#else
+        kstep(1, true, smem_raw + ((kt + 1) & 1) * kBigStage, 0, true, kt + 2, kt & 1);
+#endif
     }
     if (nk > 1) {                                     // tile nk-2: nothing left to request
-        three_steps(smem_raw + ((nk - 2) & 1) * kBigStage);
+        const unsigned char* st = smem_raw + ((nk - 2) & 1) * kBigStage;
+        kstep(0, true, st, 1, false, 0, 0);
+        kstep(1, true, st, 2, false, 0, 0);
+        kstep(0, true, st, 3, false, 0, 0);
         __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(smem_raw + ((nk - 1) & 1) * kBigStage, 0, 0);
-        mma(1);
-        interleave();
+        kstep(1, true, smem_raw + ((nk - 1) & 1) * kBigStage, 0, false, 0, 0);
     }
-    three_steps(smem_raw + ((nk - 1) & 1) * kBigStage);
-    mma(1);
+    {
+        const unsigned char* st = smem_raw + ((nk - 1) & 1) * kBigStage;
+        kstep(0, true, st, 1, false, 0, 0);
+        kstep(1, true, st, 2, false, 0, 0);
+        kstep(0, true, st, 3, false, 0, 0);
+        kstep(1, false, st, 0, false, 0, 0);
+    }
 
     // ---- epilogue: lane holds token (lane%32) and features 8*g + 4*(lane/32) + 0..3 of each block
 #pragma unroll
@@ -381,15 +384,15 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(const bf16* __restrict
         bf16* crow = C + (size_t)m * N;
         if (MODE == 2) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ / 2; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * lk;
+                    const int n = n0 + fbase[j] + 8 * g + 4 * lk;
                     if (n < N) {
                         bf16x4 o;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const float gt = acc[j][i][4 * g + e], up = acc[j + 2][i][4 * g + e];
+                            const float gt = acc[j][i][4 * g + e], up = acc[j + NJ / 2][i][4 * g + e];
                             o[e] = (bf16)(gt / (1.0f + __expf(-gt)) * up);
                         }
                         *reinterpret_cast<bf16x4*>(crow + n) = o;
@@ -397,10 +400,10 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(const bf16* __restrict
                 }
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * 128 + j * 32 + 8 * g + 4 * lk;
+                    const int n = n0 + fbase[j] + 8 * g + 4 * lk;
                     if (n < N) {
                         bf16x4 o;
                         if (MODE == 1) {
@@ -422,14 +425,14 @@ template <int MODE>
 static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
     constexpr int OUT_BN = (MODE == 2) ? 128 : 256;
     constexpr int LDS = 2 * kBigStage;
-    auto kern = gemm_big_kernel<MODE>;
+    auto kern = gemm_big_kernel<MODE, BZ_BIG_WN>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         attr_set = true;
     }
     const int tiles_m = (M + 255) / 256, tiles_n = (N + OUT_BN - 1) / OUT_BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), LDS, st, a, w, r, c, M, N, K, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K, tiles_m, tiles_n);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
