@@ -14,5 +14,6 @@ from .binding import (  # noqa: F401
     load_library,
     make_config,
     op_gemm,
+    op_gemm_workspace_bytes,
     op_rmsnorm,
 )

@@ -109,7 +109,8 @@ SIGNATURES = {
     "bz_profile_enable": (C.c_int, [_P, C.c_int]),
     "bz_profile_read": (C.c_int, [_P, C.POINTER(bz_profile)]),
     "bz_op_rmsnorm": (C.c_int, [_P, _P, _P, C.c_int, C.c_int, C.c_float, _P]),
-    "bz_op_gemm": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]),
+    "bz_op_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int]),
+    "bz_op_gemm": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P, C.c_size_t, _P]),
 }
 
 _libs: Dict[str, C.CDLL] = {}
@@ -360,8 +361,15 @@ def op_rmsnorm(x, gain, y, eps: float, stream=None, fp32_debug: bool = False) ->
         raise BzError(rc, "bz_op_rmsnorm")
 
 
-def op_gemm(mode: int, a, w, r, c, M: int, N: int, K: int, stream=None, fp32_debug: bool = False) -> None:
+def op_gemm_workspace_bytes(mode: int, M: int, N: int, K: int, fp32_debug: bool = False) -> int:
+    return int(load_library(fp32_debug).bz_op_gemm_workspace_bytes(mode, M, N, K))
+
+
+def op_gemm(mode: int, a, w, r, c, M: int, N: int, K: int, stream=None, fp32_debug: bool = False,
+            workspace=None) -> None:
     lib = load_library(fp32_debug)
-    rc = lib.bz_op_gemm(mode, _ptr(a), _ptr(w), _ptr(r), _ptr(c), M, N, K, stream.cuda_stream if stream else 0)
+    rc = lib.bz_op_gemm(mode, _ptr(a), _ptr(w), _ptr(r), _ptr(c), M, N, K, _ptr(workspace),
+                        workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                        stream.cuda_stream if stream else 0)
     if rc:
         raise BzError(rc, "bz_op_gemm")

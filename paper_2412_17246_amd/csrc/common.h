@@ -92,8 +92,11 @@ constexpr int kDecodeChunk = 256;    // KV positions per decode-attention workgr
 
 // ---- launchers (each enqueues on `st`; shapes are validated by the callers) ------------------
 void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, float eps, hipStream_t st);
+// `ws` is fp32 scratch of at least gemm_workspace_bytes(mode, M, N, K) bytes (0 for shapes that need none);
+// without it the decode-sized shapes fall back to a kernel that needs no scratch.
 void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
-                 hipStream_t st);
+                 float* ws, size_t ws_bytes, hipStream_t st);
+size_t gemm_workspace_bytes(int mode, int M, int N, int K);
 void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, const KvView& kv, int Hq,
                         hipStream_t st);
 void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,

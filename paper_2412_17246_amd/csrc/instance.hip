@@ -70,7 +70,7 @@ void layout_of(const bz_config* c, bz_layer_layout* o) {
 }
 
 struct WsLayout {
-    size_t normed, qkv, attn, act, partial, rope, slot_off, slot_cap, total;
+    size_t normed, qkv, attn, act, partial, gemm_ws, gemm_ws_bytes, rope, slot_off, slot_cap, total;
 };
 
 void ws_layout(const bz_config* c, WsLayout* w) {
@@ -84,6 +84,16 @@ void ws_layout(const bz_config* c, WsLayout* w) {
     w->act = take(T * c->ffn * e);
     const size_t chunks = (c->max_seq_len + kDecodeChunk - 1) / kDecodeChunk;
     w->partial = take((size_t)c->max_seqs * c->n_q_heads * chunks * decode_partial_stride(c->head_dim) * sizeof(float));
+    {   // fp32 scratch of the decode-sized GEMMs: the largest of the four projections
+        const int M = c->max_tokens < 64 ? c->max_tokens : 64;
+        const int qd = c->n_q_heads * c->head_dim;
+        size_t g = gemm_workspace_bytes(0, M, (int)nqkv, c->hidden);
+        size_t t = gemm_workspace_bytes(1, M, c->hidden, qd); if (t > g) g = t;
+        t = gemm_workspace_bytes(2, M, c->ffn, c->hidden); if (t > g) g = t;
+        t = gemm_workspace_bytes(1, M, c->hidden, c->ffn); if (t > g) g = t;
+        w->gemm_ws_bytes = g;
+        w->gemm_ws = take(g);
+    }
     w->rope = take((size_t)c->max_seq_len * c->head_dim * sizeof(float));
     w->slot_off = take((size_t)c->max_seqs * sizeof(int32_t));
     w->slot_cap = take((size_t)c->max_seqs * sizeof(int32_t));
@@ -655,6 +665,8 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
     act_t* attn = reinterpret_cast<act_t*>(I->wsp + I->ws.attn);
     act_t* act = reinterpret_cast<act_t*>(I->wsp + I->ws.act);
     float* partial = reinterpret_cast<float*>(I->wsp + I->ws.partial);
+    float* gws = reinterpret_cast<float*>(I->wsp + I->ws.gemm_ws);
+    const size_t gwsb = I->ws.gemm_ws_bytes;
     const float* rope = reinterpret_cast<const float*>(I->wsp + I->ws.rope);
     hipStream_t st = I->compute;
     const double e = sizeof(act_t);
@@ -675,7 +687,7 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
           launch_rmsnorm(x, g1, normed, T, sh.H, I->cfg.rms_eps, st); }
         { ProfScope p(I, BZ_K_GEMM_QKV, 2.0 * T * nqkv * sh.H, ((double)T * sh.H + (double)T * nqkv) * e + 2.0 * nqkv * sh.H);
-          launch_gemm(0, normed, wqkv, nullptr, qkv, T, nqkv, sh.H, st); }
+          launch_gemm(0, normed, wqkv, nullptr, qkv, T, nqkv, sh.H, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_ROPE_APPEND, 3.0 * T * (sh.Hq + sh.Hkv) * sh.d, (double)T * (2.0 * sh.Hq + 4.0 * sh.Hkv) * sh.d * e);
           launch_rope_append(qkv, rope, bv, kvv, sh.Hq, st); }
         if (bv.n_prefill_items > 0) {
@@ -687,13 +699,13 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
             launch_attn_decode(qkv, attn, partial, bv, kvv, sh.Hq, st);
         }
         { ProfScope p(I, BZ_K_GEMM_O, 2.0 * T * sh.H * qd, (2.0 * T * sh.H + (double)T * qd) * e + 2.0 * sh.H * qd);
-          launch_gemm(1, attn, wo, x, x, T, sh.H, qd, st); }
+          launch_gemm(1, attn, wo, x, x, T, sh.H, qd, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
           launch_rmsnorm(x, g2, normed, T, sh.H, I->cfg.rms_eps, st); }
         { ProfScope p(I, BZ_K_GEMM_GATEUP, 4.0 * T * sh.F * sh.H, ((double)T * sh.H + (double)T * sh.F) * e + 4.0 * sh.F * sh.H);
-          launch_gemm(2, normed, wgu, nullptr, act, T, sh.F, sh.H, st); }
+          launch_gemm(2, normed, wgu, nullptr, act, T, sh.F, sh.H, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_GEMM_DOWN, 2.0 * T * sh.H * sh.F, (2.0 * T * sh.H + (double)T * sh.F) * e + 2.0 * sh.H * sh.F);
-          launch_gemm(1, act, wd, x, x, T, sh.H, sh.F, st); }
+          launch_gemm(1, act, wd, x, x, T, sh.H, sh.F, gws, gwsb, st); }
         HIP_TRY(hipGetLastError());
     }
     I->stats.tokens_run += (uint64_t)T * (uint64_t)(b - a);
@@ -767,10 +779,18 @@ int bz_op_rmsnorm(const void* x, const void* gain, void* y, int T, int H, float 
     return BZ_OK;
 }
 
-int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K, void* stream) {
+size_t bz_op_gemm_workspace_bytes(int mode, int M, int N, int K) {
+    if (mode < 0 || mode > 2 || M < 0 || N < 1 || K < 8 || K % 8) return 0;
+    return gemm_workspace_bytes(mode, M, N, K);
+}
+
+int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K, void* workspace,
+               size_t workspace_bytes, void* stream) {
     if (mode < 0 || mode > 2 || !a || !w || !c || (mode == 1 && !r)) return BZ_EINVAL;
     if (M < 0 || N < 1 || K < 8 || K % 8) return BZ_EINVAL;
-    launch_gemm(mode, (const act_t*)a, (const bf16*)w, (const act_t*)r, (act_t*)c, M, N, K, (hipStream_t)stream);
+    if (workspace && ((uintptr_t)workspace & 15)) return BZ_EINVAL;
+    launch_gemm(mode, (const act_t*)a, (const bf16*)w, (const act_t*)r, (act_t*)c, M, N, K, (float*)workspace,
+                workspace_bytes, (hipStream_t)stream);
     HIP_TRY(hipGetLastError());
     return BZ_OK;
 }

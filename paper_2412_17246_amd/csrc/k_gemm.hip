@@ -435,6 +435,181 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K, tiles_m, tiles_n);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Skinny kernel for decode-sized problems (M <= 64 rows): the weights are read from HBM exactly
+// once and that read is the whole cost, so the job is to keep every CU streaming.  Work is cut
+// into 64-feature tiles times KSPLIT slices of K (a function of the shape only); each workgroup
+// streams its weight slice and the matching activation slice through a 4-deep ring of 16 KiB LDS
+// stages filled by direct global->LDS loads, multiplies with one 32x32x16 MFMA per wave and
+// k-step, and writes an fp32 partial tile.  A second kernel adds the slices in slice order and
+// applies the epilogue, so the result is deterministic.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSkStage = (64 + 64) * kBK * (int)sizeof(bf16);    // 16384
+constexpr int kSkStages = 4;
+
+__global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
+                                                             float* __restrict__ partial, int M, int Nrows, int K,
+                                                             int n_tiles, int kt_per_split) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+    const int tile_n = blockIdx.x % n_tiles, split = blockIdx.x / n_tiles;
+    const int n0 = tile_n * 64;
+    const int nk = K / kBK;
+    const int kt0 = split * kt_per_split;
+    const int kt1 = (kt0 + kt_per_split < nk) ? kt0 + kt_per_split : nk;
+    const int n = kt1 - kt0;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wf = wave >> 1, wt = wave & 1;          // feature half, token half
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+
+    // loader: chunks 0..7 hold the activation rows, 8..15 the weight rows; this wave fills chunks
+    // 2*wave, 2*wave+1 of each
+    uint32_t x_src[2], w_src[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row = (wave * 2 + j) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ swz(row);
+        int xr = row;
+        if (xr > M - 1) xr = M - 1;
+        x_src[j] = ((uint32_t)xr * (uint32_t)K + c * 8) * 2u;
+        int wr = n0 + row;
+        if (wr > Nrows - 1) wr = Nrows - 1;
+        w_src[j] = ((uint32_t)wr * (uint32_t)K + c * 8) * 2u;
+    }
+    auto issue = [&](int kt, int stage) {
+        const char* xk = reinterpret_cast<const char*>(X + (size_t)kt * kBK);
+        const char* wk = reinterpret_cast<const char*>(W + (size_t)kt * kBK);
+        unsigned char* sx = smem_raw + stage * kSkStage + wave_u * 2 * 1024;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(xk + x_src[j]), (lptr_t)(sx + j * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wk + w_src[j]), (lptr_t)(sx + 8192 + j * 1024), 16, 0, 0);
+        }
+    };
+
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const int sw = swz(lrow);
+    const int x_off = (wt * 32 + lrow) * 128;
+    const int w_off = 8192 + (wf * 32 + lrow) * 128;
+
+    // prologue: up to three tiles in flight
+    if (n > 0) issue(kt0, 0);
+    if (n > 1) issue(kt0 + 1, 1);
+    if (n > 2) issue(kt0 + 2, 2);
+    for (int i = 0; i < n; ++i) {
+        // tile i must have landed; the two tiles requested after it may still be in flight
+        if (i + 2 < n) __builtin_amdgcn_s_waitcnt(0x0078);       // vmcnt(8) lgkmcnt(0)
+        else if (i + 1 < n) __builtin_amdgcn_s_waitcnt(0x0074);  // vmcnt(4) lgkmcnt(0)
+        else __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();                            // everyone's part landed; stage (i-1)%4 is free
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + 3 < n) issue(kt0 + i + 3, (i + 3) & 3);
+        const unsigned char* st = smem_raw + (i & 3) * kSkStage;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int ko = ((ks * 2 + lk) ^ sw) * 16;
+            const bf16x8 xf = *reinterpret_cast<const bf16x8*>(st + x_off + ko);
+            const bf16x8 wfr = *reinterpret_cast<const bf16x8*>(st + w_off + ko);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr, xf, acc, 0, 0, 0);
+        }
+    }
+
+    // partial[split][m][n]: lane holds token wt*32 + lane%32, features 8g + 4*(lane/32) + 0..3
+    const int m = wt * 32 + lrow;
+    if (m < M) {
+        float* prow = partial + ((size_t)split * M + m) * Nrows;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nn = n0 + wf * 32 + 8 * g + 4 * lk;
+            if (nn < Nrows)
+                *reinterpret_cast<float4*>(prow + nn) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+        }
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_skinny_epilogue(const float* __restrict__ partial, const bf16* R, bf16* C,
+                                                            int M, int N, int Nrows, int ksplit) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;       // one thread per 4 outputs
+    const int per_row = N >> 2;
+    if (idx >= M * per_row) return;
+    const int m = idx / per_row, n = (idx - m * per_row) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f), u = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k = 0; k < ksplit; ++k) {
+        const float* prow = partial + ((size_t)k * M + m) * Nrows;
+        const float4 a = *reinterpret_cast<const float4*>(prow + n);
+        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+        if (MODE == 2) {
+            const float4 b = *reinterpret_cast<const float4*>(prow + N + n);
+            u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+        }
+    }
+    float o[4] = {s.x, s.y, s.z, s.w};
+    if (MODE == 1) {
+        const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] += (float)rv[e];
+    }
+    if (MODE == 2) {
+        const float uu[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = o[e] / (1.0f + __expf(-o[e])) * uu[e];
+    }
+    bf16x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = (bf16)o[e];
+    *reinterpret_cast<bf16x4*>(C + (size_t)m * N + n) = w;
+}
+
+struct SkinnyPlan {
+    int n_tiles, kt_per_split, ksplit;
+    size_t ws_bytes;
+};
+
+static SkinnyPlan skinny_plan(int M, int N, int K, int mode) {
+    SkinnyPlan p;
+    const int Nrows = (mode == 2) ? 2 * N : N;
+    const int nk = K / kBK;
+    p.n_tiles = (Nrows + 63) / 64;
+    int target = 512 / p.n_tiles;                 // aim at two workgroups per CU
+    if (target < 1) target = 1;
+    p.kt_per_split = (nk + target - 1) / target;
+    const int min_kt = nk < 4 ? nk : 4;           // keep the ring worth filling
+    if (p.kt_per_split < min_kt) p.kt_per_split = min_kt;
+    p.ksplit = (nk + p.kt_per_split - 1) / p.kt_per_split;
+    p.ws_bytes = (size_t)p.ksplit * M * Nrows * sizeof(float);
+    return p;
+}
+
+static bool skinny_ok(int M, int N, int K) { return M >= 1 && M <= 64 && K % kBK == 0 && N % 4 == 0; }
+
+size_t gemm_workspace_bytes(int mode, int M, int N, int K) {
+    if (!skinny_ok(M, N, K)) return 0;
+    return skinny_plan(M, N, K, mode).ws_bytes;
+}
+
+template <int MODE>
+static void launch_skinny(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
+                          hipStream_t st) {
+    const SkinnyPlan p = skinny_plan(M, N, K, MODE);
+    const int Nrows = (MODE == 2) ? 2 * N : N;
+    constexpr int LDS = kSkStages * kSkStage;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_skinny_kernel, dim3(p.n_tiles * p.ksplit), dim3(256), LDS, st, a, w, ws, M, Nrows, K,
+                       p.n_tiles, p.kt_per_split);
+    const int threads = M * (N >> 2);
+    hipLaunchKernelGGL(gemm_skinny_epilogue<MODE>, dim3((threads + 255) / 256), dim3(256), 0, st, ws, r, c, M, N, Nrows,
+                       p.ksplit);
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
 static void launch_cfg(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
     constexpr int OUT_BN = (MODE == 2) ? BN / 2 : BN;
@@ -451,12 +626,17 @@ static void launch_cfg(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 }
 
 template <int MODE>
-static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
-    // The tile shape is a function of the problem shape only, so a layer's result never depends on
-    // which range of layers a call covers.
-    if (M <= 64) {
+static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
+                        size_t ws_bytes, hipStream_t st) {
+    // The kernel and its tiling are a function of the problem shape only, so a layer's result never
+    // depends on which range of layers a call covers.
+    if (skinny_ok(M, N, K) && ws != nullptr && ws_bytes >= skinny_plan(M, N, K, MODE).ws_bytes &&
+        (uint64_t)2 * N * K < 0x7fffffffull) {
+        launch_skinny<MODE>(a, w, r, c, M, N, K, ws, st);
+    } else if (M <= 64) {
         launch_cfg<64, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
-    } else if (M > 256 && K % kBK == 0 && N % 4 == 0) {
+    } else if (M > 256 && K % kBK == 0 && N % 4 == 0 && (uint64_t)M * K < 0x7fffffffull &&
+               (uint64_t)2 * N * K < 0x7fffffffull) {     // the large-tile kernel uses 32-bit byte offsets / 2
         launch_big<MODE>(a, w, r, c, M, N, K, st);
     } else {
         launch_cfg<128, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
@@ -464,12 +644,12 @@ static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, in
 }
 
 void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
-                 hipStream_t st) {
+                 float* ws, size_t ws_bytes, hipStream_t st) {
     if (M <= 0 || N <= 0) return;
     switch (mode) {
-        case 0: launch_mode<0>(a, w, r, c, M, N, K, st); break;
-        case 1: launch_mode<1>(a, w, r, c, M, N, K, st); break;
-        default: launch_mode<2>(a, w, r, c, M, N, K, st); break;
+        case 0: launch_mode<0>(a, w, r, c, M, N, K, ws, ws_bytes, st); break;
+        case 1: launch_mode<1>(a, w, r, c, M, N, K, ws, ws_bytes, st); break;
+        default: launch_mode<2>(a, w, r, c, M, N, K, ws, ws_bytes, st); break;
     }
 }
 
@@ -500,8 +680,10 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(const float* __restrict
     }
 }
 
+size_t gemm_workspace_bytes(int, int, int, int) { return 0; }
+
 void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
-                 hipStream_t st) {
+                 float*, size_t, hipStream_t st) {
     if (M <= 0 || N <= 0) return;
     const size_t total = (size_t)M * N;
     const dim3 grid((unsigned)((total + 255) / 256));

@@ -46,6 +46,8 @@ GEMM_SHAPES = [
     (257, 4096, 512), (31, 48, 72),
     # large-tile kernel (M > 256, K a multiple of 64): ragged M, N tails, one and many K tiles
     (300, 768, 256), (700, 688, 1024), (513, 520, 64), (1030, 1024, 2048), (257, 132, 128),
+    # decode-sized problems (M <= 64, K a multiple of 64): the split-K kernel when a workspace is given
+    (64, 4096, 4096), (33, 688, 1024), (7, 260, 640), (48, 1024, 14336),
 ]
 
 
@@ -60,7 +62,16 @@ def test_gemm(torch, fp32, mode, M, N, K):
     w, wr = U.f64_to_device(rng.standard_normal((rows, K)) * (2.0 / np.sqrt(K)), False)
     r, rr = U.f64_to_device(rng.standard_normal((M, N)), fp32)
     c = torch.zeros_like(r)
-    op_gemm(mode, a, w, r if mode == 1 else None, c, M, N, K, fp32_debug=fp32)
+    from paper_2412_17246_amd import op_gemm_workspace_bytes
+    nws = op_gemm_workspace_bytes(mode, M, N, K, fp32_debug=fp32)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+    op_gemm(mode, a, w, r if mode == 1 else None, c, M, N, K, fp32_debug=fp32, workspace=ws if nws else None)
+    if nws and not fp32:
+        # the same problem without a workspace takes the kernel that needs none; both must pass
+        c2 = torch.zeros_like(r)
+        op_gemm(mode, a, w, r if mode == 1 else None, c2, M, N, K)
+    else:
+        c2 = None
     if mode == 0:
         want = O.linear(ar, wr)
     elif mode == 1:
@@ -73,6 +84,8 @@ def test_gemm(torch, fp32, mode, M, N, K):
     if not fp32:
         # bf16 output rounding alone bounds the error far below the gate; a wrong tile would not
         assert U.mixed_err(got, want, 8e-3) <= 1.0
+    if c2 is not None:
+        assert U.rel_err(U.from_device(c2), want) <= U.BF16_TOL
 
 
 def test_gemm_residual_in_place_and_identity(torch):
