@@ -108,7 +108,7 @@ def main() -> int:
     T = int(q_start[-1])
     B = len(lens)
     stream = torch.cuda.Stream()
-    inst = Instance(shape, max_seqs=B, max_seq_len=int(lens.max()) + 1, max_tokens=T, kv_tokens=int(lens.sum()) + 8,
+    inst = Instance(shape, max_seqs=B, max_seq_len=int(lens.max()) + 1, max_tokens=T, kv_tokens=int(lens.sum()) + 32 * B,
                     chunk_bytes=args.chunk_mib << 20, compute_stream=stream)
     for i, n in enumerate(lens):
         inst.kv_reserve(i, int(n))

@@ -193,8 +193,9 @@ int bz_readback_layer(bz_instance* inst, int layer, void* host);
 
 /* ---- KV slots ------------------------------------------------------------------------------ */
 
-/* Reserves room for `capacity_tokens` positions (in every layer) for slot `slot`.  BZ_ECAPACITY
- * if the arena has no contiguous room, BZ_EBUSY if the slot is reserved already. */
+/* Reserves room for `capacity_tokens` positions (in every layer) for slot `slot`; the arena hands
+ * out multiples of 32 positions, so the request is rounded up.  BZ_ECAPACITY if the arena has no
+ * contiguous room or capacity_tokens > max_seq_len, BZ_EBUSY if the slot is reserved already. */
 int bz_kv_reserve(bz_instance* inst, int slot, int capacity_tokens);
 int bz_kv_release(bz_instance* inst, int slot);
 int64_t bz_kv_free_tokens(bz_instance* inst);    /* largest reservable capacity right now */

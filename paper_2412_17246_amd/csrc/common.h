@@ -45,6 +45,25 @@ __device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
     reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
     reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
 }
+// 8 activation elements kept in their storage format (so loads in flight cost few registers)
+struct raw8_bf16 { bf16x8 v; };
+struct raw8_f32 { float4 a, b; };
+__device__ __forceinline__ void load_raw8(const bf16* p, raw8_bf16& r) { r.v = *reinterpret_cast<const bf16x8*>(p); }
+__device__ __forceinline__ void load_raw8(const float* p, raw8_f32& r) {
+    r.a = reinterpret_cast<const float4*>(p)[0];
+    r.b = reinterpret_cast<const float4*>(p)[1];
+}
+__device__ __forceinline__ float raw_get(const raw8_bf16& r, int e) { return (float)r.v[e]; }
+__device__ __forceinline__ float raw_get(const raw8_f32& r, int e) {
+    return e == 0 ? r.a.x : e == 1 ? r.a.y : e == 2 ? r.a.z : e == 3 ? r.a.w
+         : e == 4 ? r.b.x : e == 5 ? r.b.y : e == 6 ? r.b.z : r.b.w;
+}
+#ifdef BZ_FP32_DEBUG
+typedef raw8_f32 raw8_act;
+#else
+typedef raw8_bf16 raw8_act;
+#endif
+
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ void from_f32(bf16& o, float v) { o = (bf16)v; }
@@ -62,7 +81,19 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // Device-side view of the KV cache of one layer.  K part then V part; inside a part, slot s
-// starts at element slot_off[s] * Hkv * d and is laid out [Hkv][slot_cap[s]][d].
+// starts at element slot_off[s] * Hkv * d and holds Hkv heads of slot_cap[s] positions each
+// (slot_cap is a multiple of 32).
+//   V of one head: [pos][d], row-major.
+//   K of one head: blocks of 32 positions; inside a block the 8-element pieces of the head vector
+//   are stored piece-major: element (pos, j) lies at k_elem_offset(pos, j, d).  A wave reading
+//   piece c of 32 consecutive positions touches 512 contiguous bytes, and that is exactly the row
+//   operand of a 32x32x16 MFMA (lane = position, 8 consecutive k), so scores are computed from K
+//   as it lies in memory.
+__host__ __device__ inline size_t k_piece_offset(int pos, int piece, int d) {
+    return (size_t)(pos >> 5) * 32 * d + (((size_t)piece * 32 + (pos & 31)) << 3);
+}
+__host__ __device__ inline size_t k_elem_offset(int pos, int j, int d) { return k_piece_offset(pos, j >> 3, d) + (j & 7); }
+
 struct KvView {
     act_t* k;                 // layer's K part
     act_t* v;                 // layer's V part

@@ -483,7 +483,8 @@ int bz_kv_reserve(bz_instance* I, int slot, int capacity_tokens) {
     if (!I || slot < 0 || slot >= I->cfg.max_seqs || capacity_tokens < 1) return BZ_EINVAL;
     if (capacity_tokens > I->cfg.max_seq_len) return BZ_ECAPACITY;
     if (I->slots->reserved(slot)) return BZ_EBUSY;
-    if (!I->slots->reserve(slot, capacity_tokens)) return BZ_ECAPACITY;
+    // the K cache is stored in blocks of 32 positions
+    if (!I->slots->reserve(slot, ((int64_t)capacity_tokens + 31) / 32 * 32)) return BZ_ECAPACITY;
     return push_slot(I, slot);
 }
 
@@ -500,7 +501,7 @@ int bz_kv_release(bz_instance* I, int slot) {
 
 int64_t bz_kv_free_tokens(bz_instance* I) {
     if (!I) return BZ_EINVAL;
-    return I->slots->largest_free();
+    return I->slots->largest_free() / 32 * 32;
 }
 
 static int kv_xfer(bz_instance* I, int layer, int slot, int pos0, int n, const void* k, const void* v, void* ko,
@@ -508,7 +509,7 @@ static int kv_xfer(bz_instance* I, int layer, int slot, int pos0, int n, const v
     if (!I || layer < 0 || layer >= I->sh.L || slot < 0 || slot >= I->cfg.max_seqs || pos0 < 0 || n < 0) return BZ_EINVAL;
     if (to_cache ? (!k || !v) : (!ko || !vo)) return BZ_EINVAL;
     if (!I->slots->reserved(slot)) return BZ_ESTATE;
-    if ((int64_t)pos0 + n > I->slots->capacity(slot)) return BZ_ECAPACITY;
+    if ((int64_t)pos0 + n > I->slots->capacity(slot) || (int64_t)pos0 + n > I->cfg.max_seq_len) return BZ_ECAPACITY;
     if (I->dry) return BZ_ESTATE;
     if (n == 0) return BZ_OK;
     const size_t bytes = (size_t)n * I->sh.Hkv * I->sh.d * sizeof(act_t);
@@ -645,6 +646,7 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         if (!I->slots->reserved(slot)) return BZ_ESTATE;
         const int qlen = batch->q_start[s + 1] - batch->q_start[s];
         if ((int64_t)batch->kv_before[s] + qlen > I->slots->capacity(slot)) return BZ_ECAPACITY;
+        if ((int64_t)batch->kv_before[s] + qlen > I->cfg.max_seq_len) return BZ_ECAPACITY;
     }
     for (int l = a; l < b; ++l)
         if (I->state[l] == kNone) return BZ_ENOTLOADED;

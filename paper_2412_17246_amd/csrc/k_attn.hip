@@ -1,8 +1,8 @@
 // Causal attention over the KV cache: a tiled MFMA kernel for sequences with several new tokens
 // (prefill) and a split-KV kernel plus fixed-order combine for sequences with one (decode).
 //
-// Cache layout per (layer, slot, kv head): K[pos][d] and V[pos][d], pos-major.  Query head h reads
-// kv head h / (Hq/Hkv).  A query at absolute position p sees keys 0..p.  Scores are scaled by
+// Cache layout per (layer, slot, kv head): V[pos][d]; K in blocks of 32 positions stored piece-major
+// (k_piece_offset), which is the MFMA row-operand order.  Query head h reads kv head h / (Hq/Hkv).  A query at absolute position p sees keys 0..p.  Scores are scaled by
 // 1/sqrt(d); softmax is evaluated in base 2 (scores pre-multiplied by log2 e).
 #include "common.h"
 
@@ -23,11 +23,10 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out,
                                                            BatchView bv, KvView kv, int Hq, float scale_log2) {
     constexpr int BQ = kPrefillTileQ, BK = 64;
-    constexpr int KROW = D + 8;      // padded LDS rows (elements)
-    constexpr int VROW = BK + 8;
+    constexpr int VROW = BK + 8;     // padded LDS rows (elements)
     constexpr int DB = D / 32;       // 32-wide blocks of the head dim
     constexpr int KS = D / 16;       // MFMA k-steps over the head dim
-    __shared__ __attribute__((aligned(16))) bf16 Ks[BK * KROW];
+    __shared__ __attribute__((aligned(16))) bf16 Ks[BK * D];      // two 32-position blocks, piece-major as in the cache
     __shared__ __attribute__((aligned(16))) bf16 Vt[D * VROW];
 
     const int item = blockIdx.x, h = blockIdx.y;
@@ -75,16 +74,17 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restric
     for (int tile = 0; tile < ntiles; ++tile) {
         const int kbase = tile * BK;
         __syncthreads();                                     // all waves are done with the previous tile
-        {   // K tile, row-major
-            constexpr int VPR = D / 8;                       // 16-byte vectors per row
-            constexpr int RPP = 256 / VPR;                   // rows per pass
+        {   // K tile: two 32-position blocks copied as they lie in the cache (a block past the last
+            // visible key is replaced by the last visible block; its scores are masked anyway)
+            constexpr int VPB = 32 * D / 8;                  // 16-byte vectors per block
 #pragma unroll
-            for (int p = 0; p < BK / RPP; ++p) {
-                const int row = tid / VPR + p * RPP, vec = tid % VPR;
-                int kp = kbase + row;
-                if (kp > kv_end - 1) kp = kv_end - 1;
-                *reinterpret_cast<uint4*>(&Ks[row * KROW + vec * 8]) =
-                    *reinterpret_cast<const uint4*>(Kc + (size_t)kp * D + vec * 8);
+            for (int p = 0; p < 2 * VPB / 256; ++p) {
+                const int v = tid + p * 256;
+                const int blk = v / VPB, off = v % VPB;
+                int kb = (kbase >> 5) + blk;
+                if (kb > ((kv_end - 1) >> 5)) kb = (kv_end - 1) >> 5;
+                *reinterpret_cast<uint4*>(&Ks[v * 8]) =
+                    *reinterpret_cast<const uint4*>(Kc + (size_t)kb * 32 * D + off * 8);
             }
         }
         {   // V tile, transposed into Vt[d][kv]
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restric
                 for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(kb * 32 + lq) * KROW + ks * 16 + lh * 8]);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[kb * 32 * D + ((ks * 2 + lh) * 32 + lq) * 8]);
                     sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
                 }
             }
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(64) void attn_naive_kernel(const float* __restrict_
     float mx = -INFINITY;
     for (int j = lane; j <= pos; j += 64) {
         float a = 0.f;
-        for (int e = 0; e < D; ++e) a = fmaf(q[e], Kc[(size_t)j * D + e], a);
+        for (int e = 0; e < D; ++e) a = fmaf(q[e], Kc[k_elem_offset(j, e, D)], a);
         a *= scale_log2;
         sc[j] = a;
         mx = fmaxf(mx, a);
@@ -260,11 +260,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
     constexpr int CH = kDecodeChunk;
     constexpr int LPR = D / 8;            // lanes per V row
     constexpr int RPI = 64 / LPR;         // V rows per wave load
-    __shared__ float qs[G][D];
-    __shared__ float ps[G][CH];
-    __shared__ float red_m[4][G];
-    __shared__ float red_l[4][G];
+    constexpr int NSTEP = 64 / RPI;       // V loads per lane for the wave's 64 positions
+    __shared__ float ps[4][G][64];
+    __shared__ float wmx[4][G];
+    __shared__ float wsum[4][G];
     __shared__ float osh[4][G][D];
+#ifdef BZ_FP32_DEBUG
+    __shared__ float qs[G][D];
+#endif
 
     const int chunk = blockIdx.x, kvh = blockIdx.y, di = blockIdx.z;
     const int s = bv.decode_seqs[di];
@@ -278,71 +281,139 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
     const act_t* Kc = kv.k + head_base;
     const act_t* Vc = kv.v + head_base;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const act_t* q = qkv + (size_t)t * (Hq + 2 * Hkv) * D + (size_t)kvh * G * D;    // G query heads, contiguous
 
+    // Each wave owns 64 positions and runs on its own: no workgroup barrier until the four partial
+    // results are merged.  Rows past the end are read from the last valid row (so all loads are
+    // unconditional and in bounds) and get probability zero.
+    const int w0 = c0 + wave * 64;
+    const int sub = lane / LPR, dv = (lane % LPR) * 8;
+    raw8_act vv[NSTEP];
+#pragma unroll
+    for (int stp = 0; stp < NSTEP; ++stp) {           // V rows first: they stay in flight under the score math
+        int vp = w0 + stp * RPI + sub;
+        if (vp > len - 1) vp = len - 1;
+        load_raw8(Vc + (size_t)vp * D + dv, vv[stp]);
+    }
+
+#ifndef BZ_FP32_DEBUG
+    // Scores on the matrix cores: S^T[pos, g] = K[pos, :] . q[g, :].  A K row is the MFMA's row
+    // operand exactly as it lies in memory (lane = position, 16 bytes per k-step), so it goes from
+    // global memory straight into the instruction; q fills G of the 32 columns, the rest are zero.
     {
-        const act_t* q = qkv + (size_t)t * (Hq + 2 * Hkv) * D + (size_t)kvh * G * D;
+        const int lq = lane & 31, lh = lane >> 5;
+        bf16x8 qf[D / 16];
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+            if (lq < G) qf[ks] = *reinterpret_cast<const bf16x8*>(q + lq * D + ks * 16 + lh * 8);
+            else
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qf[ks][e] = (bf16)0.f;
+        }
+        f32x16 sacc[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            int kb = (w0 >> 5) + rb;                         // 32-position block; past the end: the last valid one
+            if (kb > ((len - 1) >> 5)) kb = (len - 1) >> 5;
+            const bf16* kr = Kc + (size_t)kb * 32 * D + (lh * 32 + lq) * 8;
+            bf16x8 kf[D / 16];
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(kr + ks * 2 * 32 * 8);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[rb][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks)
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc[rb], 0, 0, 0);
+        }
+        // lane (g = lane%32, h = lane/32) holds positions rb*32 + 8*(r/4) + 4h + r%4 of head g
+        float m = -INFINITY;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int pl = rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                const float sg = (w0 + pl < len) ? sacc[rb][r] * scale_log2 : -INFINITY;
+                sacc[rb][r] = sg;
+                m = fmaxf(m, sg);
+            }
+        m = fmaxf(m, __shfl_xor(m, 32, kWave));
+        float l = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = (sacc[rb][r] == -INFINITY) ? 0.f : exp2f(sacc[rb][r] - m);
+                sacc[rb][r] = p;
+                l += p;
+            }
+        l += __shfl_xor(l, 32, kWave);
+        if (lq < G) {
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4)
+                    *reinterpret_cast<float4*>(&ps[wave][lq][rb * 32 + 8 * r4 + 4 * lh]) =
+                        make_float4(sacc[rb][4 * r4], sacc[rb][4 * r4 + 1], sacc[rb][4 * r4 + 2], sacc[rb][4 * r4 + 3]);
+            if (lh == 0) {
+                wmx[wave][lq] = m;
+                wsum[wave][lq] = l;
+            }
+        }
+    }
+#else
+    {
         for (int i = tid; i < G * D / 8; i += 256) {
             float v[8];
             load8(q + i * 8, v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) (&qs[0][0])[i * 8 + e] = v[e];
         }
-    }
-    __syncthreads();
-
-    const int pos = c0 + tid;
-    const bool valid = pos < len;
-    float sc[G];
+        __syncthreads();
+        const int pos = w0 + lane;
+        const bool valid = pos < len;
+        const int kpos = valid ? pos : len - 1;
+        float sc[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) sc[g] = 0.f;
-    if (valid) {
-        const act_t* kr = Kc + (size_t)pos * D;
-#pragma unroll
+        for (int g = 0; g < G; ++g) sc[g] = 0.f;
         for (int c = 0; c < D / 8; ++c) {
             float kk[8];
-            load8(kr + c * 8, kk);
+            load8(Kc + k_piece_offset(kpos, c, D), kk);
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) sc[g] = fmaf(kk[e], qs[g][c * 8 + e], sc[g]);
         }
-    }
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        sc[g] = valid ? sc[g] * scale_log2 : -INFINITY;
-        const float wm = wave_max(sc[g]);
-        if (lane == 0) red_m[wave][g] = wm;
+        for (int g = 0; g < G; ++g) {
+            const float sg = valid ? sc[g] * scale_log2 : -INFINITY;
+            const float m = wave_max(sg);
+            const float p = valid ? exp2f(sg - m) : 0.f;
+            ps[wave][g][lane] = p;
+            const float l = wave_sum(p);
+            if (lane == 0) {
+                wmx[wave][g] = m;
+                wsum[wave][g] = l;
+            }
+        }
     }
-    __syncthreads();
-    float mx[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        mx[g] = fmaxf(fmaxf(red_m[0][g], red_m[1][g]), fmaxf(red_m[2][g], red_m[3][g]));
-        const float p = valid ? exp2f(sc[g] - mx[g]) : 0.f;
-        ps[g][tid] = p;
-        const float ws = wave_sum(p);
-        if (lane == 0) red_l[wave][g] = ws;
-    }
-    __syncthreads();
+#endif
 
     float o[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[g][e] = 0.f;
-    const int sub = lane / LPR, dv = (lane % LPR) * 8;
-#pragma unroll 4
-    for (int stp = 0; stp < 64 / RPI; ++stp) {
-        const int prow = wave * 64 + stp * RPI + sub;
-        if (c0 + prow < len) {
-            float vv[8];
-            load8(Vc + (size_t)(c0 + prow) * D + dv, vv);
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float pw = ps[g][prow];
+    for (int stp = 0; stp < NSTEP; ++stp) {
+        const int prow = stp * RPI + sub;
+        float vf[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[g][e] = fmaf(pw, vv[e], o[g][e]);
-            }
+        for (int e = 0; e < 8; ++e) vf[e] = raw_get(vv[stp], e);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float pw = ps[wave][g][prow];       // written by this wave only
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[g][e] = fmaf(pw, vf[e], o[g][e]);
         }
     }
 #pragma unroll
@@ -361,17 +432,25 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
             for (int e = 0; e < 8; ++e) osh[wave][g][dv + e] = o[g][e];
     }
     __syncthreads();
+    // merge the four waves in wave order
     const int PS = decode_partial_stride(D);
     for (int i = tid; i < G * D; i += 256) {
         const int g = i / D, dd = i - g * D;
-        const float v = ((osh[0][g][dd] + osh[1][g][dd]) + osh[2][g][dd]) + osh[3][g][dd];
-        partial[(((size_t)di * Hq + kvh * G + g) * bv.decode_chunks + chunk) * PS + dd] = v;
+        const float M = fmaxf(fmaxf(wmx[0][g], wmx[1][g]), fmaxf(wmx[2][g], wmx[3][g]));
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc = fmaf(osh[w][g][dd], exp2f(wmx[w][g] - M), acc);
+        partial[(((size_t)di * Hq + kvh * G + g) * bv.decode_chunks + chunk) * PS + dd] = acc;
     }
     if (tid < G) {
         const int g = tid;
+        const float M = fmaxf(fmaxf(wmx[0][g], wmx[1][g]), fmaxf(wmx[2][g], wmx[3][g]));
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) L = fmaf(wsum[w][g], exp2f(wmx[w][g] - M), L);
         float* pp = partial + (((size_t)di * Hq + kvh * G + g) * bv.decode_chunks + chunk) * PS;
-        pp[D] = fmaxf(fmaxf(red_m[0][g], red_m[1][g]), fmaxf(red_m[2][g], red_m[3][g]));
-        pp[D + 1] = ((red_l[0][g] + red_l[1][g]) + red_l[2][g]) + red_l[3][g];
+        pp[D] = M;
+        pp[D + 1] = L;
     }
 }
 

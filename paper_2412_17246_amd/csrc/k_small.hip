@@ -92,9 +92,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
                 store8(hp + half + j0, o_hi);
             } else {
                 const int kvh = head - Hq;
-                act_t* dst = kv.k + slot_base + ((size_t)kvh * cap + pos) * d;
-                store8(dst + j0, o_lo);
-                store8(dst + half + j0, o_hi);
+                act_t* dst = kv.k + slot_base + (size_t)kvh * cap * d;
+                store8(dst + k_piece_offset(pos, j0 >> 3, d), o_lo);
+                store8(dst + k_piece_offset(pos, (half + j0) >> 3, d), o_hi);
             }
         } else {
             const int w = u - rot_units;
@@ -132,16 +132,18 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(const act_t* __restrict
         const int kvh = w / (d >> 3);
         const int j0 = (w - kvh * (d >> 3)) * 8;
         const size_t lin = (size_t)tok * Hkv * d + (size_t)kvh * d + j0;
-        const size_t cac = slot_base + ((size_t)kvh * cap + pos0 + tok) * d + j0;
+        const size_t head = slot_base + (size_t)kvh * cap * d;
+        const size_t cac_v = head + (size_t)(pos0 + tok) * d + j0;
+        const size_t cac_k = head + k_piece_offset(pos0 + tok, j0 >> 3, d);
         float a[8], b[8];
         if (to_cache) {
             load8(src_k + lin, a);
             load8(src_v + lin, b);
-            store8(kv.k + cac, a);
-            store8(kv.v + cac, b);
+            store8(kv.k + cac_k, a);
+            store8(kv.v + cac_v, b);
         } else {
-            load8(kv.k + cac, a);
-            load8(kv.v + cac, b);
+            load8(kv.k + cac_k, a);
+            load8(kv.v + cac_v, b);
             store8(dst_k + lin, a);
             store8(dst_v + lin, b);
         }

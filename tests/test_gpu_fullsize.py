@@ -58,7 +58,7 @@ def test_7b_layer_bench_batch_sampled_sequences(torch):
     q_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
     T = int(q_start[-1])
     bits = W.layer_weights_bits(base, 0)
-    inst = U.make_instance(s, max_seqs=8, max_seq_len=int(lens.max()) + 1, max_tokens=T, kv_tokens=T + 8)
+    inst = U.make_instance(s, max_seqs=8, max_seq_len=int(lens.max()) + 1, max_tokens=T, kv_tokens=T + 8 * 32)
     for i, n in enumerate(lens):
         inst.kv_reserve(i, int(n))
     inst.load_layer(0, inst.pinned_blob(inst.pack_layer(bits)))
@@ -88,7 +88,7 @@ def test_8b_gqa_decode_step_full_batch(torch):
     B = 64
     lens = W.uniform_lengths(base.seed, B, 256, 4096)
     bits = W.layer_weights_bits(base, 0)
-    inst = U.make_instance(s, max_seqs=B, max_seq_len=4097 + 1, max_tokens=B, kv_tokens=int(lens.sum()) + B)
+    inst = U.make_instance(s, max_seqs=B, max_seq_len=4097 + 1, max_tokens=B, kv_tokens=int(lens.sum()) + 33 * B)
     okv = O.OracleKV()
     for i, n in enumerate(lens):
         n = int(n)

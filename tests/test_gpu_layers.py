@@ -175,7 +175,7 @@ def test_nowait_reports_not_ready_and_frontier_is_prefix(torch):
     ms0, ms1 = inst.layer_ready_ms(0), inst.layer_ready_ms(1)
     assert 0.0 <= ms1 <= ms0
     # capacity errors: more new tokens than the slot holds
-    big = inst.batch([0, 16], [0], [4])
+    big = inst.batch([0, 16], [0], [20])         # 20 + 16 > the 32 positions the slot holds
     xb = U.to_device(W.hidden_bits(s, 16), False)
     with pytest.raises(Exception) as ei:
         inst.run_layers(0, 2, big, xb)
@@ -197,7 +197,7 @@ def _mixed_case(torch, s, fp32, seqs):
     """seqs: list of (new_tokens, kv_len_before).  Sequences with a non-empty cache get seeded
     pre-existing K/V in every layer, written through the C ABI."""
     os_ = U.oracle_shape(s)
-    total_cap = sum(n + b for n, b in seqs) + 8
+    total_cap = sum((n + b + 31) // 32 * 32 for n, b in seqs) + 32      # slots are multiples of 32 positions
     T = sum(n for n, _ in seqs)
     inst = U.make_instance(s, max_seqs=len(seqs), max_seq_len=max(n + b for n, b in seqs) + 1,
                            max_tokens=T, kv_tokens=total_cap, fp32=fp32)
@@ -206,7 +206,7 @@ def _mixed_case(torch, s, fp32, seqs):
     U.load_all_layers(inst, s)
     okv = O.OracleKV()
     for i, (n, before) in enumerate(seqs):
-        inst.kv_reserve(i, n + before)
+        inst.kv_reserve(i, max(n + before, 1))
         if before:
             for l in range(s.L):
                 kb, vb = W.kv_prefill_bits(s, l, i, before)

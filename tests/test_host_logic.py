@@ -103,17 +103,17 @@ def _status(fn, *a):
 
 def test_kv_slot_bookkeeping(dry):
     assert dry.kv_free_tokens() == 256
-    dry.kv_reserve(0, 100)
-    dry.kv_reserve(1, 100)
+    dry.kv_reserve(0, 90)                                        # rounded up to 96 positions
+    dry.kv_reserve(1, 96)
     assert _status(dry.kv_reserve, 1, 10) == "BZ_EBUSY"
     assert _status(dry.kv_reserve, 2, 101) == "BZ_ECAPACITY"     # above max_seq_len
-    assert _status(dry.kv_reserve, 2, 57) == "BZ_ECAPACITY"      # 56 tokens left
-    assert dry.kv_free_tokens() == 56
+    assert _status(dry.kv_reserve, 2, 65) == "BZ_ECAPACITY"      # 64 positions left
+    assert dry.kv_free_tokens() == 64
     dry.kv_release(0)
-    assert dry.kv_free_tokens() == 100                           # two runs: 100 and 56, not adjacent
-    dry.kv_reserve(2, 56)
+    assert dry.kv_free_tokens() == 96                            # two runs: 96 and 64, not adjacent
+    dry.kv_reserve(2, 64)
     dry.kv_release(1)
-    assert dry.kv_free_tokens() == 200                           # runs 0..100 and 100..200 merged
+    assert dry.kv_free_tokens() == 192                           # runs 0..96 and 96..192 merged
     dry.kv_release(2)
     assert dry.kv_free_tokens() == 256
     assert _status(dry.kv_release, 2) == "BZ_ESTATE"
