@@ -260,10 +260,15 @@ def run_decode(args, torch, Instance):
     inst = make_instance()
     blobs = []
     for l in range(shape.L):
-        blobs.append(gen_layer_blob_gpu(torch, inst, shape, gen, pinned=False))
+        blob = gen_layer_blob_gpu(torch, inst, shape, gen, pinned=False)
         torch.cuda.synchronize()
-        inst.load_layer_from_device(l, blobs[-1])
-    inst.sync()
+        inst.load_layer_from_device(l, blob)
+        inst.sync()
+        if args.split:
+            blobs.append(blob)            # the split pair loads the same bytes later
+        else:
+            inst._keep.clear()            # layer is resident: the staging blob can go
+            del blob
     gen_kv = torch.Generator(device="cuda")
     gen_kv.manual_seed(base.seed + 100)
     for i, n in enumerate(lens):

@@ -291,3 +291,45 @@ def test_prefill_then_decode_matches_longer_prefill_on_the_gpu(torch):
         return out
     a, b = run(False), run(True)
     assert U.rel_err(b, a) <= U.BF16_TOL
+
+
+def test_gqa_decode_live_split_is_bit_exact_over_steps(torch):
+    """8B-GQA-like shape (4 query heads per kv head, d = 128), 4 layers, continuous decode of 6
+    sequences whose caches straddle the 256-position chunks; a live split at layer 2 with two
+    instance handles and a boundary hand-off every step must reproduce the unsplit bits."""
+    s = W.DecoderShape("gqa_split", L=4, H=512, Hq=8, Hkv=2, d=128, F=1024, rope_base=500000.0, seed=31)
+    lens = [5, 255, 256, 300, 511, 700]
+    B, steps, k = len(lens), 5, 2
+
+    def fresh(layers):
+        inst = U.make_instance(s, max_seqs=B, max_seq_len=768, max_tokens=B, kv_tokens=sum(lens) + 64 * B)
+        U.load_all_layers(inst, s, layers)
+        for i, n in enumerate(lens):
+            inst.kv_reserve(i, n + steps)
+            for l in layers:
+                kb, vb = W.kv_prefill_bits(s, l, i, n)
+                inst.kv_write(l, i, 0, n, kb, vb)
+        return inst
+
+    whole, tgt, src = fresh(range(4)), fresh(range(0, k)), fresh(range(k, 4))
+    bw = whole.batch(list(range(B + 1)), list(range(B)), lens)
+    bs = tgt.batch(list(range(B + 1)), list(range(B)), lens)
+    for step in range(steps):
+        bits = W.hidden_bits(s, B, step=40 + step)
+        a, b = U.to_device(bits, False), U.to_device(bits, False)
+        c = torch.zeros_like(b)
+        buf = np.empty((B, s.H), dtype=np.uint16)
+        torch.cuda.synchronize()
+        whole.run_layers(0, 4, bw, a)
+        whole.batch_advance(bw)
+        tgt.run_layers(0, k, bs, b)
+        tgt.export_boundary(b, B, buf)          # through host memory: waits for the target's stream
+        src.import_boundary(c, B, buf)
+        src.run_layers(k, 4, bs, c)
+        src.sync()
+        tgt.batch_advance(bs)                   # shared batch: advance once, after both halves ran
+        tgt.sync()
+        whole.sync()
+        assert torch.equal(a.view(torch.int16), c.view(torch.int16)), step
+    for inst in (whole, tgt, src):
+        inst.close()
