@@ -40,6 +40,11 @@ import workloads as W  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0
+# Bytes moved per launch of the dominant kernel of the default workload (gate/up projection, M = 6768):
+# rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE of this script, scaled by what the same counters read for
+# a 1 GiB device copy (x2.0 and x1.0); see profiles/gemm_big_kernel_7b_prefill_stream.txt.  L2-miss traffic
+# summed over the 8 XCD L2s, mostly served by the Infinity Cache.
+MEASURED_TRAFFIC = {("7b", 32, 6768, "gemm_gateup"): 2.105e9 + 0.150e9}
 
 
 # ------------------------------------------------------------------------------- helpers
@@ -218,6 +223,7 @@ def run_prefill_stream(args, torch, Instance):
     resident_s = (time.perf_counter() - t0) / 3
 
     roof, all_tf = gemm_roofline(prof)
+    roof["traffic"] = MEASURED_TRAFFIC.get((shape.name, shape.L, T, roof["kernel"]))
     out = base_record("prefill tokens/s on partially loaded model", T * args.steps / total, "tokens/s", args,
                       ms_per_step,
                       f"{shape.name}-shaped decoder, {shape.L} layers streamed from pinned host memory while a packed "
