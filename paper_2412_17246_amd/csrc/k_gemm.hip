@@ -353,11 +353,7 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         kstep(0, true, st, 3, false, 0, 0);
         __builtin_amdgcn_s_waitcnt(0x0070);           // vmcnt(0) lgkmcnt(0): tile kt+1 landed, own reads of tile kt done
         __syncthreads();
-#ifdef BZ_EXP_NOLOAD
-        kstep(1, true, smem_raw + ((kt + 1) & 1) * kBigStage, 0, false, kt + 2, kt & 1);
-#else
         kstep(1, true, smem_raw + ((kt + 1) & 1) * kBigStage, 0, true, kt + 2, kt & 1);
-#endif
     }
     if (nk > 1) {                                     // tile nk-2: nothing left to request
         const unsigned char* st = smem_raw + ((nk - 2) & 1) * kBigStage;
