@@ -244,6 +244,52 @@ int bz_stats_read(bz_instance* inst, bz_stats* out);
 int bz_profile_enable(bz_instance* inst, int on);
 int bz_profile_read(bz_instance* inst, bz_profile* out);
 
+/* ---- request scheduling during live scaling ------------------------------------------------- */
+/* Section 5.2: while the target instance is still loading, request batches are split between the
+ * target (the layers it has) and the source (the rest).  Two policies:
+ *   BZ_ZZ_BEST_EFFORT  each batch runs as many layers as are resident on the target when it is
+ *                      dispatched there (at most half of the model), the rest on the source, in
+ *                      arrival order;
+ *   BZ_ZZ_ZIGZAG       the ILP-free ZigZag policy: the target runs ONE layer of the first batch (in
+ *                      arrival order) whose next layer is resident and keeps the batch queued; the
+ *                      source, whenever it is idle, takes the first unfinished batch and runs all of
+ *                      its remaining layers.  When both are free at once the source chooses first;
+ *                      the source never takes a batch whose layer the target is executing.
+ * Results do not depend on the schedule: every batch's output equals the unsplit run bit for bit. */
+enum { BZ_ZZ_ZIGZAG = 0, BZ_ZZ_BEST_EFFORT = 1 };
+typedef struct bz_zz bz_zz;
+typedef struct bz_zz_event {
+    int32_t request;     /* index returned by bz_zz_submit */
+    int32_t instance;    /* 0 = target, 1 = source */
+    int32_t layer_a;     /* layers [layer_a, layer_b) were enqueued */
+    int32_t layer_b;
+    int32_t frontier;    /* the target's frontier when the decision was taken */
+    float   t_ms;        /* host time since bz_zz_run started */
+} bz_zz_event;
+
+/* Decision logic alone, in virtual time (no GPU): one layer of one batch takes one time unit on
+ * either instance, layer k of the target is resident from k * load_time on, the source is busy
+ * until source_free_at.  Writes, per request, the layers run on the target and the time it left
+ * the source.  Same decision code as bz_zz_run. */
+int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, double source_free_at,
+                   int32_t* layers_on_target, double* finish_time);
+
+/* A scheduler over two instances holding the same model (the source fully resident; the target
+ * loading: the caller issues bz_load_layer on it before or while bz_zz_run runs).  Both instances
+ * must have KV slots reserved for every submitted batch. */
+int bz_zz_create(bz_instance* target, bz_instance* source, int policy, bz_zz** out);
+int bz_zz_destroy(bz_zz* zz);
+/* Queues a batch (arrival order = submission order).  `hidden_target` (device, [T,H]) holds the
+ * input and is the buffer the target works in; `hidden_source` (device, [T,H], distinct) receives
+ * the activation at the hand-off and holds the final output.  Returns the request index (>= 0). */
+int bz_zz_submit(bz_zz* zz, const bz_batch* batch, void* hidden_target, void* hidden_source);
+/* Runs every submitted batch to completion under the policy, polling the target's frontier and the
+ * two compute streams; returns when all outputs are complete. */
+int bz_zz_run(bz_zz* zz);
+int bz_zz_layers_on_target(const bz_zz* zz, int request);
+/* Copies up to max_events decision records; returns the total number recorded. */
+int bz_zz_trace(const bz_zz* zz, bz_zz_event* out, int max_events);
+
 /* ---- single operations (the layer's steps, exposed for tests and micro-benchmarks) ---------- */
 /* All pointers are device memory; work is enqueued on `stream` (a hipStream_t, NULL = default).
  * Activations are activation elements (bf16, or float in the fp32 debug build); weights bf16. */

@@ -5,6 +5,10 @@ its ctypes binding."""
 from .binding import (  # noqa: F401
     BZ_FLAG_DRY_RUN,
     BZ_RUN_NOWAIT,
+    BZ_ZZ_BEST_EFFORT,
+    BZ_ZZ_ZIGZAG,
+    Scheduler,
+    zz_simulate,
     Batch,
     BzError,
     Instance,

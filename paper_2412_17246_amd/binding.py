@@ -65,6 +65,13 @@ class bz_stats(C.Structure):
                 ("layer_launches", C.c_uint64), ("frontier", C.c_int32), ("reserved", C.c_int32)]
 
 
+class bz_zz_event(C.Structure):
+    _fields_ = [("request", C.c_int32), ("instance", C.c_int32), ("layer_a", C.c_int32), ("layer_b", C.c_int32),
+                ("frontier", C.c_int32), ("t_ms", C.c_float)]
+
+
+BZ_ZZ_ZIGZAG = 0
+BZ_ZZ_BEST_EFFORT = 1
 _NK = len(KERNEL_CLASSES)
 
 
@@ -108,6 +115,14 @@ SIGNATURES = {
     "bz_stats_read": (C.c_int, [_P, C.POINTER(bz_stats)]),
     "bz_profile_enable": (C.c_int, [_P, C.c_int]),
     "bz_profile_read": (C.c_int, [_P, C.POINTER(bz_profile)]),
+    "bz_zz_simulate": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.POINTER(C.c_int32),
+                                 C.POINTER(C.c_double)]),
+    "bz_zz_create": (C.c_int, [_P, _P, C.c_int, C.POINTER(_P)]),
+    "bz_zz_destroy": (C.c_int, [_P]),
+    "bz_zz_submit": (C.c_int, [_P, _P, _P, _P]),
+    "bz_zz_run": (C.c_int, [_P]),
+    "bz_zz_layers_on_target": (C.c_int, [_P, C.c_int]),
+    "bz_zz_trace": (C.c_int, [_P, C.POINTER(bz_zz_event), C.c_int]),
     "bz_op_rmsnorm": (C.c_int, [_P, _P, _P, C.c_int, C.c_int, C.c_float, _P]),
     "bz_op_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int]),
     "bz_op_gemm": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P, C.c_size_t, _P]),
@@ -352,6 +367,67 @@ class Instance:
         self._check(self.lib.bz_profile_read(self.handle, C.byref(p)), "bz_profile_read")
         return {name: {"launches": int(p.launches[i]), "ms": float(p.ms[i]), "flops": float(p.flops[i]),
                        "bytes": float(p.bytes[i])} for i, name in enumerate(KERNEL_CLASSES)}
+
+
+def zz_simulate(policy: int, n_layers: int, n_requests: int, load_time: float, source_free_at: float = 0.0,
+                fp32_debug: bool = False):
+    """Virtual-time run of the scheduler's decision code: (layers on target, finish time) per request."""
+    lib = load_library(fp32_debug)
+    T = (C.c_int32 * n_requests)()
+    fin = (C.c_double * n_requests)()
+    rc = lib.bz_zz_simulate(policy, n_layers, n_requests, load_time, source_free_at, T, fin)
+    if rc:
+        raise BzError(rc, "bz_zz_simulate")
+    return list(T), list(fin)
+
+
+class Scheduler:
+    """Two-instance request scheduler (best-effort or ZigZag) over one target and one source."""
+
+    def __init__(self, target: "Instance", source: "Instance", policy: int = BZ_ZZ_ZIGZAG):
+        self.lib = target.lib
+        h = _P()
+        rc = self.lib.bz_zz_create(target.handle, source.handle, policy, C.byref(h))
+        if rc:
+            raise BzError(rc, "bz_zz_create")
+        self.handle = h
+        self._keep = []
+
+    def submit(self, batch: Batch, hidden_target, hidden_source) -> int:
+        self._keep.append((batch, hidden_target, hidden_source))
+        rc = self.lib.bz_zz_submit(self.handle, batch.handle, _ptr(hidden_target), _ptr(hidden_source))
+        if rc < 0:
+            raise BzError(rc, "bz_zz_submit")
+        return rc
+
+    def run(self) -> None:
+        rc = self.lib.bz_zz_run(self.handle)
+        if rc:
+            raise BzError(rc, "bz_zz_run", self.lib.bz_last_hip_error().decode() if rc == -6 else "")
+
+    def layers_on_target(self, request: int) -> int:
+        rc = self.lib.bz_zz_layers_on_target(self.handle, request)
+        if rc < 0:
+            raise BzError(rc, "bz_zz_layers_on_target")
+        return rc
+
+    def trace(self):
+        n = self.lib.bz_zz_trace(self.handle, None, 0)
+        buf = (bz_zz_event * max(n, 1))()
+        self.lib.bz_zz_trace(self.handle, buf, n)
+        return [dict(request=e.request, instance=e.instance, layer_a=e.layer_a, layer_b=e.layer_b,
+                     frontier=e.frontier, t_ms=e.t_ms) for e in buf[:n]]
+
+    def close(self):
+        if self.handle:
+            self.lib.bz_zz_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def op_rmsnorm(x, gain, y, eps: float, stream=None, fp32_debug: bool = False) -> None:

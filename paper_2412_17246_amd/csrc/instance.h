@@ -1,0 +1,69 @@
+// Internal definitions of the instance and batch objects, shared by the translation units that
+// implement the C ABI.
+#pragma once
+
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "kv_slots.h"
+
+namespace bz {
+
+struct Shape {
+    int L, H, Hq, Hkv, d, F;
+    int nqkv() const { return (Hq + 2 * Hkv) * d; }
+};
+
+struct WsLayout {
+    size_t normed, qkv, attn, act, partial, gemm_ws, gemm_ws_bytes, rope, slot_off, slot_cap, total;
+};
+
+enum LayerState { kNone = 0, kLoading = 1, kResident = 2 };
+
+struct ProfRec {
+    int cls;
+    hipEvent_t e0, e1;
+    double flops, bytes;
+};
+
+// records a failed HIP call for bz_last_hip_error() and returns BZ_EHIP
+int hip_fail(hipError_t e, const char* what);
+
+}  // namespace bz
+
+struct bz_batch {
+    int B = 0, T = 0;
+    bool all_decode = false;
+    std::vector<int32_t> q_start, seq_slot, kv_before;
+    int n_prefill_items = 0, n_decode = 0;
+    std::vector<int32_t> decode_seqs;
+    double prefill_sq = 0;            // sum over prefill sequences of visible (query, key) pairs
+    void* dev = nullptr;              // one allocation holding all device arrays
+    int32_t *d_q_start = nullptr, *d_seq_slot = nullptr, *d_kv_before = nullptr, *d_token_seq = nullptr,
+            *d_items = nullptr, *d_decode = nullptr;
+};
+
+struct bz_instance {
+    bz_config cfg;
+    bz::Shape sh;
+    bz_sizes sz;
+    bz_layer_layout lay;
+    bz::WsLayout ws;
+    bool dry = false;
+    hipStream_t compute = nullptr, copy = nullptr;
+    bool own_compute = false, own_copy = false;
+    unsigned char* weights = nullptr;
+    unsigned char* kv = nullptr;
+    unsigned char* wsp = nullptr;
+    bool own_weights = false, own_kv = false, own_ws = false;
+    std::vector<int> state;
+    std::vector<hipEvent_t> ev;
+    hipEvent_t t0 = nullptr;
+    bool clock_started = false;
+    bz::KvSlots* slots = nullptr;
+    bz_stats stats;
+    bool prof_on = false;
+    std::vector<bz::ProfRec> prof;
+    std::vector<hipEvent_t> ev_pool;
+};

@@ -8,8 +8,7 @@
 #include <string>
 #include <vector>
 
-#include "common.h"
-#include "kv_slots.h"
+#include "instance.h"
 
 using namespace bz;
 
@@ -17,12 +16,19 @@ namespace {
 
 thread_local std::string g_hip_err;
 
+}  // namespace
+
+namespace bz {
 int hip_fail(hipError_t e, const char* what) {
     char buf[256];
     snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
     g_hip_err = buf;
     return BZ_EHIP;
 }
+}  // namespace bz
+
+namespace {
+
 #define HIP_TRY(call)                                   \
     do {                                                \
         hipError_t e__ = (call);                        \
@@ -31,10 +37,6 @@ int hip_fail(hipError_t e, const char* what) {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-struct Shape {
-    int L, H, Hq, Hkv, d, F;
-    int nqkv() const { return (Hq + 2 * Hkv) * d; }
-};
 
 int validate(const bz_config* c) {
     if (!c) return BZ_EINVAL;
@@ -69,9 +71,6 @@ void layout_of(const bz_config* c, bz_layer_layout* o) {
     o->total = p;
 }
 
-struct WsLayout {
-    size_t normed, qkv, attn, act, partial, gemm_ws, gemm_ws_bytes, rope, slot_off, slot_cap, total;
-};
 
 void ws_layout(const bz_config* c, WsLayout* w) {
     const size_t T = c->max_tokens, e = sizeof(act_t);
@@ -100,51 +99,11 @@ void ws_layout(const bz_config* c, WsLayout* w) {
     w->total = p;
 }
 
-enum LayerState { kNone = 0, kLoading = 1, kResident = 2 };
 
-struct ProfRec {
-    int cls;
-    hipEvent_t e0, e1;
-    double flops, bytes;
-};
 
 }  // namespace
 
-struct bz_batch {
-    int B = 0, T = 0;
-    bool all_decode = false;
-    std::vector<int32_t> q_start, seq_slot, kv_before;
-    int n_prefill_items = 0, n_decode = 0;
-    std::vector<int32_t> decode_seqs;
-    double prefill_sq = 0;            // sum over prefill sequences of visible (query, key) pairs
-    void* dev = nullptr;              // one allocation holding all device arrays
-    int32_t *d_q_start = nullptr, *d_seq_slot = nullptr, *d_kv_before = nullptr, *d_token_seq = nullptr,
-            *d_items = nullptr, *d_decode = nullptr;
-};
 
-struct bz_instance {
-    bz_config cfg;
-    Shape sh;
-    bz_sizes sz;
-    bz_layer_layout lay;
-    WsLayout ws;
-    bool dry = false;
-    hipStream_t compute = nullptr, copy = nullptr;
-    bool own_compute = false, own_copy = false;
-    unsigned char* weights = nullptr;
-    unsigned char* kv = nullptr;
-    unsigned char* wsp = nullptr;
-    bool own_weights = false, own_kv = false, own_ws = false;
-    std::vector<int> state;
-    std::vector<hipEvent_t> ev;
-    hipEvent_t t0 = nullptr;
-    bool clock_started = false;
-    KvSlots* slots = nullptr;
-    bz_stats stats;
-    bool prof_on = false;
-    std::vector<ProfRec> prof;
-    std::vector<hipEvent_t> ev_pool;
-};
 
 namespace {
 

@@ -150,3 +150,21 @@ def test_batch_descriptor_validation(lib):
     assert make([0, 2], [0], [-1])[0] == -1         # negative cache length
     assert make([0, 0], [0], [0])[0] == -1          # no tokens at all
     assert lib.bz_batch_create(None, C.byref(C.c_void_p())) == -1
+
+
+def test_scheduler_decisions_match_the_oracle_in_virtual_time():
+    """The C++ decision code, driven in virtual time, against the CPU oracle's simulation: integer
+    configurations and finish times must agree exactly, for both policies."""
+    from oracle import zigzag as Z
+    cases = [(7, 7, 6.0, 1.0), (4, 3, 2.0, 0.0), (8, 10, 3.0, 5.0), (5, 6, 0.5, 2.0), (6, 4, 10.0, 0.0),
+             (3, 8, 1.0, 1.0), (12, 5, 7.0, 30.0), (32, 12, 6.0, 1.0), (80, 6, 2.5, 0.0), (2, 2, 0.0, 0.0)]
+    for L, n, load, free in cases:
+        T, fin = B.zz_simulate(B.BZ_ZZ_ZIGZAG, L, n, load, free)
+        want = Z.simulate_zigzag(L, n, load, free)
+        assert T == want.T and fin == want.finish, (L, n, load, free)
+        T, fin = B.zz_simulate(B.BZ_ZZ_BEST_EFFORT, L, n, load, free)
+        want = Z.simulate_best_effort(L, n, load, free)
+        assert T == want.T and fin == want.finish, (L, n, load, free)
+    lib = B.load_library()
+    assert lib.bz_zz_simulate(5, 3, 3, 1.0, 0.0, (C.c_int32 * 3)(), (C.c_double * 3)()) == -1     # unknown policy
+    assert lib.bz_zz_create(None, None, 0, C.byref(C.c_void_p())) == -1
