@@ -452,12 +452,75 @@ def run_mixed_ttft(args, torch, Instance):
     return out
 
 
+def run_zigzag(args, torch, Instance):
+    """Several queued prefill batches (2000 tokens each, the batch size of the paper's example) served by a
+    loaded source instance and a target instance whose layers stream in from pinned host memory, under the
+    ZigZag or the best-effort policy.  Both instances share this one GPU, so the run shows correctness and
+    scheduling overhead, not the two-GPU throughput gain."""
+    from paper_2412_17246_amd import BZ_ZZ_BEST_EFFORT, BZ_ZZ_ZIGZAG, Scheduler
+    base = W.CONFIGS[args.shape]
+    shape = with_layers(base, args.layers)
+    n_req, tok = args.requests if args.requests != 8 else 6, args.fixed_len or 2000
+    stream_t, stream_s = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def make(stream):
+        inst = Instance(shape, max_seqs=n_req, max_seq_len=tok + 1, max_tokens=tok, kv_tokens=n_req * (tok + 32),
+                        chunk_bytes=args.chunk_mib << 20, compute_stream=stream)
+        for r in range(n_req):
+            inst.kv_reserve(r, tok)
+        return inst
+
+    tgt, src = make(stream_t), make(stream_s)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(base.seed)
+    blobs = [gen_layer_blob_gpu(torch, tgt, shape, gen) for _ in range(shape.L)]
+    for l in range(shape.L):
+        src.load_layer(l, blobs[l])
+    src.sync()
+    x0 = [torch.from_numpy(W.hidden_bits(shape, tok, step=r).view(np.int16).copy()).view(torch.bfloat16).cuda()
+          for r in range(n_req)]
+    results = {}
+    for name, policy in (("zigzag", BZ_ZZ_ZIGZAG), ("best_effort", BZ_ZZ_BEST_EFFORT)):
+        times = []
+        for it in range(args.warmup + args.steps):
+            for l in range(shape.L):
+                tgt.unload_layer(l)
+            xt = [x.clone() for x in x0]
+            xs = [torch.empty_like(x) for x in x0]
+            sched = Scheduler(tgt, src, policy)
+            batches = [tgt.batch([0, tok], [r], [0]) for r in range(n_req)]
+            for r in range(n_req):
+                sched.submit(batches[r], xt[r], xs[r])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for l in range(shape.L):
+                tgt.load_layer(l, blobs[l])
+            sched.run()
+            dt = time.perf_counter() - t0
+            if it >= args.warmup:
+                times.append(dt)
+            cfgs = [sched.layers_on_target(r) for r in range(n_req)]
+            n_events = len(sched.trace())
+            sched.close()
+        results[name] = {"ms": float(np.mean(times)) * 1e3, "layers_on_target": cfgs, "decisions": n_events}
+    zz = results["zigzag"]
+    out = base_record("prefill tokens/s on partially loaded model", n_req * tok / (zz["ms"] * 1e-3), "tokens/s", args,
+                      zz["ms"],
+                      f"{shape.name}-shaped decoder, {n_req} queued prefill batches of {tok} tokens, source instance resident, "
+                      f"target instance streaming {shape.L} layers from pinned host memory, ZigZag policy (one GPU shared)",
+                      {"shape": shape.name, "layers": shape.L, "requests": n_req, "tokens_per_request": tok})
+    out["policies"] = results
+    tgt.close()
+    src.close()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="prefill_stream", choices=["prefill_stream", "decode", "mixed_ttft"])
+    ap.add_argument("--workload", default="prefill_stream", choices=["prefill_stream", "decode", "mixed_ttft", "zigzag"])
     ap.add_argument("--shape", default="7b", choices=list(W.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the shape (debugging)")
     ap.add_argument("--requests", type=int, default=8)
@@ -482,7 +545,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
-    fn = {"prefill_stream": run_prefill_stream, "decode": run_decode, "mixed_ttft": run_mixed_ttft}[args.workload]
+    fn = {"prefill_stream": run_prefill_stream, "decode": run_decode, "mixed_ttft": run_mixed_ttft,
+          "zigzag": run_zigzag}[args.workload]
     print(json.dumps(fn(args, torch, Instance)))
     return 0
 
