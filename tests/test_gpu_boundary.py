@@ -1,0 +1,108 @@
+"""Boundary behaviour on the GPU: ingest byte-exactness for several chunk sizes and sources, KV
+import/export round trips through the cache layout, slot reuse, error codes that need a device."""
+import numpy as np
+import pytest
+
+import workloads as W
+from tests import _util as U
+
+pytestmark = pytest.mark.gpu
+
+TINY = W.CONFIGS["tiny"]
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+@pytest.mark.parametrize("chunk", [0, 4096, 1 << 20, 1000003])
+def test_ingest_is_byte_exact_for_any_chunk_size(torch, chunk):
+    inst = U.make_instance(TINY, max_seqs=1, max_seq_len=32, max_tokens=8, kv_tokens=32, chunk_bytes=chunk)
+    rng = np.random.default_rng(chunk + 1)
+    blobs = [rng.integers(0, 256, inst.layer_bytes, dtype=np.uint8) for _ in range(TINY.L)]
+    pinned = [inst.pinned_blob(b) for b in blobs]
+    for l in (1, 0):                                   # out of order
+        inst.load_layer(l, pinned[l])
+    for l in range(TINY.L):
+        assert np.array_equal(inst.readback_layer(l), blobs[l])
+    st = inst.stats()
+    assert st["bytes_ingested"] == TINY.L * inst.layer_bytes and st["frontier"] == TINY.L
+    inst.close()
+
+
+def test_device_resident_source_and_reload(torch):
+    inst = U.make_instance(TINY, max_seqs=1, max_seq_len=32, max_tokens=8, kv_tokens=32)
+    blob = np.random.default_rng(3).integers(0, 256, inst.layer_bytes, dtype=np.uint8)
+    dev = torch.from_numpy(blob).cuda()
+    torch.cuda.synchronize()
+    inst.load_layer_from_device(0, dev)
+    assert np.array_equal(inst.readback_layer(0), blob)
+    inst.unload_layer(0)
+    assert inst.frontier() == 0 and not inst.layer_ready(0)
+    blob2 = blob[::-1].copy()
+    inst.load_layer(0, inst.pinned_blob(blob2))        # the same slot can be loaded again after unload
+    assert np.array_equal(inst.readback_layer(0), blob2)
+    inst.close()
+
+
+@pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
+@pytest.mark.parametrize("shape", [TINY, W.DecoderShape("g", L=2, H=256, Hq=8, Hkv=2, d=128, F=256, seed=51)],
+                         ids=["d64", "d128"])
+def test_kv_write_read_round_trip(torch, fp32, shape):
+    """Token-major K/V in, cache layout inside (K in 32-position piece-major blocks), token-major out;
+    partial ranges that straddle block boundaries; host and device buffers."""
+    s = shape
+    inst = U.make_instance(s, max_seqs=3, max_seq_len=200, max_tokens=8, kv_tokens=512, fp32=fp32)
+    inst.kv_reserve(0, 100)
+    inst.kv_reserve(2, 190)
+    n = 150
+    kb, vb = W.kv_prefill_bits(s, 1, 2, n)
+    as_host = (lambda b: W.f32_from_bf16_bits(b)) if fp32 else (lambda b: b)
+    inst.kv_write(1, 2, 0, 40, as_host(kb[:40]), as_host(vb[:40]))                 # host source
+    kd, vd = U.to_device(kb[40:], fp32), U.to_device(vb[40:], fp32)
+    torch.cuda.synchronize()
+    inst.kv_write(1, 2, 40, n - 40, kd, vd)                                        # device source
+    inst.sync()
+    ko = np.empty((n - 7, s.Hkv, s.d), dtype=np.float32 if fp32 else np.uint16)
+    vo = np.empty_like(ko)
+    inst.kv_read(1, 2, 7, n - 7, ko, vo)
+    assert np.array_equal(ko, as_host(kb[7:])) and np.array_equal(vo, as_host(vb[7:]))
+    with pytest.raises(Exception) as ei:
+        inst.kv_write(1, 2, 180, 20, as_host(kb[:20]), as_host(vb[:20]))
+    assert "BZ_ECAPACITY" in str(ei.value)
+    with pytest.raises(Exception) as ei:
+        inst.kv_write(1, 1, 0, 4, as_host(kb[:4]), as_host(vb[:4]))                # slot 1 not reserved
+    assert "BZ_ESTATE" in str(ei.value)
+    # releasing and re-reserving hands the same room out again
+    free_before = inst.kv_free_tokens()
+    inst.kv_release(0)
+    inst.kv_reserve(1, 64)
+    assert inst.kv_free_tokens() <= free_before + 128
+    inst.close()
+
+
+def test_empty_ranges_and_single_token(torch):
+    s = TINY
+    inst = U.make_instance(s, max_seqs=2, max_seq_len=64, max_tokens=8, kv_tokens=128)
+    U.load_all_layers(inst, s)
+    inst.kv_reserve(0, 8)
+    x = U.to_device(W.hidden_bits(s, 1), False)
+    before = x.clone()
+    torch.cuda.synchronize()
+    batch = inst.batch([0, 1], [0], [0])
+    inst.run_layers(1, 1, batch, x)                    # empty layer range: nothing happens
+    inst.sync()
+    assert torch.equal(x.view(torch.int16), before.view(torch.int16))
+    inst.run_layers(0, 2, batch, x)                    # one token, empty cache
+    inst.sync()
+    assert torch.isfinite(x.float()).all() and not torch.equal(x.view(torch.int16), before.view(torch.int16))
+    with pytest.raises(Exception) as ei:
+        inst.run_layers(0, 3, batch, x)
+    assert "BZ_EINVAL" in str(ei.value)
+    with pytest.raises(Exception) as ei:
+        inst.run_layers(0, 2, inst.batch([0, 1], [1], [0]), x)     # slot never reserved
+    assert "BZ_ESTATE" in str(ei.value)
+    inst.close()
