@@ -128,6 +128,18 @@ void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, fl
 void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
                  float* ws, size_t ws_bytes, hipStream_t st);
 size_t gemm_workspace_bytes(int mode, int M, int N, int K);
+// Decode-sized problems only: computes the split-K partial sums partial[ksplit][M][Nrows] (Nrows = 2N
+// in SwiGLU mode) into `ws` and returns ksplit, leaving the slice-order reduction and the epilogue
+// to the consumer kernel; returns 0 (and does nothing) when the shape does not take that path.
+int launch_gemm_partial(int mode, const act_t* a, const bf16* w, int M, int N, int K, float* ws, size_t ws_bytes,
+                        hipStream_t st);
+// x[T,H] += sum over slices of partial[k][T][H] (slice order), rounded to the activation type and
+// stored; then, unless gain is null, y = rmsnorm(x) * gain exactly as launch_rmsnorm would compute it.
+void launch_reduce_residual_rmsnorm(act_t* x, const float* partial, int ksplit, const bf16* gain, act_t* y, int T,
+                                    int H, float eps, hipStream_t st);
+// launch_rope_append on a projection output that is still in split-K partial form
+void launch_rope_append_reduce(act_t* qkv, const float* partial, int ksplit, const float* rope_tab,
+                               const BatchView& bv, const KvView& kv, int Hq, hipStream_t st);
 void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, const KvView& kv, int Hq,
                         hipStream_t st);
 void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,

@@ -634,6 +634,7 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
     double decode_kv = 0;
     for (int s : batch->decode_seqs) decode_kv += (double)(batch->kv_before[s] + 1);
 
+    int pending_down = 0;        // split-K slices of the previous layer's down projection still to be folded into x
     for (int l = a; l < b; ++l) {
         if (I->state[l] != kResident) HIP_TRY(hipStreamWaitEvent(st, I->ev[l], 0));
         const unsigned char* wl = layer_ptr(I, l);
@@ -645,12 +646,20 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         const bf16* wd = (const bf16*)(wl + I->lay.wd);
         const KvView kvv = kv_view(I, l);
         const int nqkv = sh.nqkv(), qd = sh.Hq * sh.d;
+        // Decode-sized batches: the projections leave split-K partial sums in `gws` and the kernel that
+        // consumes the projection folds them (QKV -> rotary/append; O and down -> residual + next norm).
+        // The stored values are the same bits the unfused kernels produce.
         { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
-          launch_rmsnorm(x, g1, normed, T, sh.H, I->cfg.rms_eps, st); }
+          if (pending_down > 0) launch_reduce_residual_rmsnorm(x, gws, pending_down, g1, normed, T, sh.H, I->cfg.rms_eps, st);
+          else launch_rmsnorm(x, g1, normed, T, sh.H, I->cfg.rms_eps, st);
+          pending_down = 0; }
+        int ks_qkv = 0;
         { ProfScope p(I, BZ_K_GEMM_QKV, 2.0 * T * nqkv * sh.H, ((double)T * sh.H + (double)T * nqkv) * e + 2.0 * nqkv * sh.H);
-          launch_gemm(0, normed, wqkv, nullptr, qkv, T, nqkv, sh.H, gws, gwsb, st); }
+          ks_qkv = launch_gemm_partial(0, normed, wqkv, T, nqkv, sh.H, gws, gwsb, st);
+          if (ks_qkv == 0) launch_gemm(0, normed, wqkv, nullptr, qkv, T, nqkv, sh.H, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_ROPE_APPEND, 3.0 * T * (sh.Hq + sh.Hkv) * sh.d, (double)T * (2.0 * sh.Hq + 4.0 * sh.Hkv) * sh.d * e);
-          launch_rope_append(qkv, rope, bv, kvv, sh.Hq, st); }
+          if (ks_qkv > 0) launch_rope_append_reduce(qkv, gws, ks_qkv, rope, bv, kvv, sh.Hq, st);
+          else launch_rope_append(qkv, rope, bv, kvv, sh.Hq, st); }
         if (bv.n_prefill_items > 0) {
             ProfScope p(I, BZ_K_ATTN_PREFILL, 4.0 * sh.Hq * sh.d * batch->prefill_sq, 0.0);
             launch_attn_prefill(qkv, attn, bv, kvv, sh.Hq, st);
@@ -659,14 +668,23 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
             ProfScope p(I, BZ_K_ATTN_DECODE, 4.0 * sh.Hq * sh.d * decode_kv, decode_kv * 2.0 * sh.Hkv * sh.d * e);
             launch_attn_decode(qkv, attn, partial, bv, kvv, sh.Hq, st);
         }
+        int ks_o = 0;
         { ProfScope p(I, BZ_K_GEMM_O, 2.0 * T * sh.H * qd, (2.0 * T * sh.H + (double)T * qd) * e + 2.0 * sh.H * qd);
-          launch_gemm(1, attn, wo, x, x, T, sh.H, qd, gws, gwsb, st); }
+          ks_o = launch_gemm_partial(1, attn, wo, T, sh.H, qd, gws, gwsb, st);
+          if (ks_o == 0) launch_gemm(1, attn, wo, x, x, T, sh.H, qd, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
-          launch_rmsnorm(x, g2, normed, T, sh.H, I->cfg.rms_eps, st); }
+          if (ks_o > 0) launch_reduce_residual_rmsnorm(x, gws, ks_o, g2, normed, T, sh.H, I->cfg.rms_eps, st);
+          else launch_rmsnorm(x, g2, normed, T, sh.H, I->cfg.rms_eps, st); }
         { ProfScope p(I, BZ_K_GEMM_GATEUP, 4.0 * T * sh.F * sh.H, ((double)T * sh.H + (double)T * sh.F) * e + 4.0 * sh.F * sh.H);
           launch_gemm(2, normed, wgu, nullptr, act, T, sh.F, sh.H, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_GEMM_DOWN, 2.0 * T * sh.H * sh.F, (2.0 * T * sh.H + (double)T * sh.F) * e + 2.0 * sh.H * sh.F);
-          launch_gemm(1, act, wd, x, x, T, sh.H, sh.F, gws, gwsb, st); }
+          pending_down = launch_gemm_partial(1, act, wd, T, sh.H, sh.F, gws, gwsb, st);
+          if (pending_down == 0) launch_gemm(1, act, wd, x, x, T, sh.H, sh.F, gws, gwsb, st); }
+        HIP_TRY(hipGetLastError());
+    }
+    if (pending_down > 0) {      // last layer of the range: finish the residual stream without a norm
+        ProfScope p(I, BZ_K_RMSNORM, 1.0 * T * sh.H, 2.0 * T * sh.H * e);
+        launch_reduce_residual_rmsnorm(x, gws, pending_down, nullptr, normed, T, sh.H, I->cfg.rms_eps, st);
         HIP_TRY(hipGetLastError());
     }
     I->stats.tokens_run += (uint64_t)T * (uint64_t)(b - a);

@@ -587,11 +587,16 @@ size_t gemm_workspace_bytes(int mode, int M, int N, int K) {
     return skinny_plan(M, N, K, mode).ws_bytes;
 }
 
-template <int MODE>
-static void launch_skinny(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
-                          hipStream_t st) {
-    const SkinnyPlan p = skinny_plan(M, N, K, MODE);
-    const int Nrows = (MODE == 2) ? 2 * N : N;
+static bool skinny_applies(int mode, int M, int N, int K, const float* ws, size_t ws_bytes) {
+    return skinny_ok(M, N, K) && ws != nullptr && ws_bytes >= skinny_plan(M, N, K, mode).ws_bytes &&
+           (uint64_t)2 * N * K < 0x7fffffffull;
+}
+
+// Split-K partial sums only: partial[ksplit][M][Nrows] (Nrows = 2N in SwiGLU mode).  The caller
+// folds the slices in slice order, either with gemm_skinny_epilogue or fused into the next kernel.
+static int launch_skinny_partial(int mode, const bf16* a, const bf16* w, int M, int N, int K, float* ws, hipStream_t st) {
+    const SkinnyPlan p = skinny_plan(M, N, K, mode);
+    const int Nrows = (mode == 2) ? 2 * N : N;
     constexpr int LDS = kSkStages * kSkStage;
     static bool attr_set = false;
     if (!attr_set) {
@@ -601,9 +606,23 @@ static void launch_skinny(const bf16* a, const bf16* w, const bf16* r, bf16* c, 
     }
     hipLaunchKernelGGL(gemm_skinny_kernel, dim3(p.n_tiles * p.ksplit), dim3(256), LDS, st, a, w, ws, M, Nrows, K,
                        p.n_tiles, p.kt_per_split);
+    return p.ksplit;
+}
+
+int launch_gemm_partial(int mode, const act_t* a, const bf16* w, int M, int N, int K, float* ws, size_t ws_bytes,
+                        hipStream_t st) {
+    if (M <= 0 || N <= 0 || !skinny_applies(mode, M, N, K, ws, ws_bytes)) return 0;
+    return launch_skinny_partial(mode, a, w, M, N, K, ws, st);
+}
+
+template <int MODE>
+static void launch_skinny(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
+                          hipStream_t st) {
+    const int ksplit = launch_skinny_partial(MODE, a, w, M, N, K, ws, st);
+    const int Nrows = (MODE == 2) ? 2 * N : N;
     const int threads = M * (N >> 2);
     hipLaunchKernelGGL(gemm_skinny_epilogue<MODE>, dim3((threads + 255) / 256), dim3(256), 0, st, ws, r, c, M, N, Nrows,
-                       p.ksplit);
+                       ksplit);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int MODE>
@@ -626,8 +645,7 @@ static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, in
                         size_t ws_bytes, hipStream_t st) {
     // The kernel and its tiling are a function of the problem shape only, so a layer's result never
     // depends on which range of layers a call covers.
-    if (skinny_ok(M, N, K) && ws != nullptr && ws_bytes >= skinny_plan(M, N, K, MODE).ws_bytes &&
-        (uint64_t)2 * N * K < 0x7fffffffull) {
+    if (skinny_applies(MODE, M, N, K, ws, ws_bytes)) {
         launch_skinny<MODE>(a, w, r, c, M, N, K, ws, st);
     } else if (M <= 64) {
         launch_cfg<64, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
@@ -677,6 +695,7 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(const float* __restrict
 }
 
 size_t gemm_workspace_bytes(int, int, int, int) { return 0; }
+int launch_gemm_partial(int, const act_t*, const bf16*, int, int, int, float*, size_t, hipStream_t) { return 0; }
 
 void launch_gemm(int mode, const act_t* a, const bf16* w, const act_t* r, act_t* c, int M, int N, int K,
                  float*, size_t, hipStream_t st) {

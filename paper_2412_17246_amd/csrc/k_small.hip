@@ -8,23 +8,57 @@ namespace bz {
 // RMSNorm: one workgroup per token row.  Sum of squares in fp32 (wave shuffle reduction, then a
 // fixed-order sum over the waves), y = (x * rstd) * gain rounded once to the activation type.
 // ---------------------------------------------------------------------------------------------
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void rmsnorm_kernel(const act_t* __restrict__ x,
-                                                          const bf16* __restrict__ gain,
+// sum over split-K slices, in slice order, of 8 consecutive partial sums of row m.  Loads go out four
+// slices at a time (a slice index past the end re-reads the last slice; its value is not added).
+__device__ __forceinline__ void reduce8(const float* __restrict__ partial, int ksplit, size_t slice_stride,
+                                        size_t off, float (&s)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] = 0.f;
+    for (int k0 = 0; k0 < ksplit; k0 += 4) {
+        float4 a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = (k0 + u < ksplit) ? k0 + u : ksplit - 1;
+            a[u] = *reinterpret_cast<const float4*>(partial + k * slice_stride + off);
+            b[u] = *reinterpret_cast<const float4*>(partial + k * slice_stride + off + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k0 + u < ksplit) {
+                s[0] += a[u].x; s[1] += a[u].y; s[2] += a[u].z; s[3] += a[u].w;
+                s[4] += b[u].x; s[5] += b[u].y; s[6] += b[u].z; s[7] += b[u].w;
+            }
+    }
+}
+
+// REDUCE: the row of x is first completed as x + (sum of split-K slices), rounded and stored; the
+// norm then works on the stored values, so its result is bit-identical to a separate norm kernel.
+template <int THREADS, bool REDUCE>
+__global__ __launch_bounds__(THREADS) void rmsnorm_kernel(act_t* __restrict__ x, const float* __restrict__ partial,
+                                                          int ksplit, int T, const bf16* __restrict__ gain,
                                                           act_t* __restrict__ y, int H, float eps) {
     constexpr int NW = THREADS / kWave;
     __shared__ float red[NW];
     const int row = blockIdx.x;
-    const act_t* xr = x + (size_t)row * H;
+    act_t* xr = x + (size_t)row * H;
     act_t* yr = y + (size_t)row * H;
     const int nvec = H >> 3;
     float ss = 0.f;
     for (int i = threadIdx.x; i < nvec; i += THREADS) {
         float v[8];
         load8(xr + i * 8, v);
+        if (REDUCE) {
+            float s[8];
+            reduce8(partial, ksplit, (size_t)T * H, (size_t)row * H + i * 8, s);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+            for (int e = 0; e < 8; ++e) v[e] = s[e] + v[e];
+            store8(xr + i * 8, v);
+            load8(xr + i * 8, v);                  // the rounded values (this thread's own store)
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(v[e], v[e], ss);
     }
+    if (gain == nullptr) return;
     ss = wave_sum(ss);
     if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = ss;
     __syncthreads();
@@ -44,10 +78,21 @@ __global__ __launch_bounds__(THREADS) void rmsnorm_kernel(const act_t* __restric
 
 void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, float eps, hipStream_t st) {
     if (T <= 0) return;
+    act_t* xm = const_cast<act_t*>(x);       // not written without REDUCE
     if (H >= 2048) {
-        hipLaunchKernelGGL(rmsnorm_kernel<256>, dim3(T), dim3(256), 0, st, x, gain, y, H, eps);
+        hipLaunchKernelGGL((rmsnorm_kernel<256, false>), dim3(T), dim3(256), 0, st, xm, nullptr, 0, T, gain, y, H, eps);
     } else {
-        hipLaunchKernelGGL(rmsnorm_kernel<64>, dim3(T), dim3(64), 0, st, x, gain, y, H, eps);
+        hipLaunchKernelGGL((rmsnorm_kernel<64, false>), dim3(T), dim3(64), 0, st, xm, nullptr, 0, T, gain, y, H, eps);
+    }
+}
+
+void launch_reduce_residual_rmsnorm(act_t* x, const float* partial, int ksplit, const bf16* gain, act_t* y, int T,
+                                    int H, float eps, hipStream_t st) {
+    if (T <= 0) return;
+    if (H >= 2048) {
+        hipLaunchKernelGGL((rmsnorm_kernel<256, true>), dim3(T), dim3(256), 0, st, x, partial, ksplit, T, gain, y, H, eps);
+    } else {
+        hipLaunchKernelGGL((rmsnorm_kernel<64, true>), dim3(T), dim3(64), 0, st, x, partial, ksplit, T, gain, y, H, eps);
     }
 }
 
@@ -57,8 +102,9 @@ void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, fl
 // to the cache.  Pairs are (j, j + d/2); the cos/sin table is [max_seq_len][d/2][2] floats built
 // on the host in float64.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qkv,
-                                                          const float* __restrict__ tab, BatchView bv,
+template <bool REDUCE>
+__global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qkv, const float* __restrict__ partial,
+                                                          int ksplit, const float* __restrict__ tab, BatchView bv,
                                                           KvView kv, int Hq) {
     const int t = blockIdx.x;
     const int s = bv.token_seq[t];
@@ -70,6 +116,22 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
     const int nqkv = (Hq + 2 * Hkv) * d;
     act_t* row = qkv + (size_t)t * nqkv;
     const float* cs = tab + (size_t)pos * d;   // [half][2]
+    // REDUCE: the projection output is still split-K partial sums; fold them in slice order and round
+    // to the activation type first, exactly as the separate epilogue kernel would have
+    auto fetch8 = [&](int col, float (&v)[8]) {
+        if (REDUCE) {
+            float s8[8];
+            reduce8(partial, ksplit, (size_t)bv.T * nqkv, (size_t)t * nqkv + col, s8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                act_t r;
+                from_f32(r, s8[e]);
+                v[e] = to_f32(r);
+            }
+        } else {
+            load8(row + col, v);
+        }
+    };
     const int units_per_head = half >> 3;      // 8 pairs per unit
     const int rot_units = (Hq + Hkv) * units_per_head;
     const int v_units = Hkv * (d >> 3);
@@ -79,8 +141,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
             const int j0 = (u - head * units_per_head) * 8;
             act_t* hp = row + head * d;
             float lo[8], hi[8], o_lo[8], o_hi[8];
-            load8(hp + j0, lo);
-            load8(hp + half + j0, hi);
+            fetch8(head * d + j0, lo);
+            fetch8(head * d + half + j0, hi);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float c = cs[(j0 + e) * 2], sn = cs[(j0 + e) * 2 + 1];
@@ -101,7 +163,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
             const int kvh = w / (d >> 3);
             const int j0 = (w - kvh * (d >> 3)) * 8;
             float v[8];
-            load8(row + (Hq + Hkv + kvh) * d + j0, v);
+            fetch8((Hq + Hkv + kvh) * d + j0, v);
             store8(kv.v + slot_base + ((size_t)kvh * cap + pos) * d + j0, v);
         }
     }
@@ -110,7 +172,14 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
 void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, const KvView& kv, int Hq,
                         hipStream_t st) {
     if (bv.T <= 0) return;
-    hipLaunchKernelGGL(rope_append_kernel, dim3(bv.T), dim3(256), 0, st, qkv, rope_tab, bv, kv, Hq);
+    hipLaunchKernelGGL(rope_append_kernel<false>, dim3(bv.T), dim3(256), 0, st, qkv, nullptr, 0, rope_tab, bv, kv, Hq);
+}
+
+void launch_rope_append_reduce(act_t* qkv, const float* partial, int ksplit, const float* rope_tab,
+                               const BatchView& bv, const KvView& kv, int Hq, hipStream_t st) {
+    if (bv.T <= 0) return;
+    hipLaunchKernelGGL(rope_append_kernel<true>, dim3(bv.T), dim3(256), 0, st, qkv, partial, ksplit, rope_tab, bv, kv,
+                       Hq);
 }
 
 // ---------------------------------------------------------------------------------------------
