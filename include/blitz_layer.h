@@ -88,7 +88,7 @@ typedef struct bz_config {
     void*   compute_stream;  /* hipStream_t for kernels, or NULL: the library creates one */
     void*   copy_stream;     /* hipStream_t for ingest, or NULL: the library creates one */
     void*   weights_arena;   /* device, >= bz_sizes.weights_arena_bytes, 256-byte aligned; NULL: library allocates */
-    void*   kv_arena;        /* device, >= bz_sizes.kv_arena_bytes; NULL: library allocates */
+    void*   kv_arena;        /* device, >= bz_sizes.kv_arena_bytes; NULL: library allocates; cleared by bz_create */
     void*   workspace;       /* device, >= bz_sizes.workspace_bytes; NULL: library allocates */
     size_t  weights_arena_bytes;
     size_t  kv_arena_bytes;

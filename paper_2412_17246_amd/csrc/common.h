@@ -82,17 +82,24 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // Device-side view of the KV cache of one layer.  K part then V part; inside a part, slot s
 // starts at element slot_off[s] * Hkv * d and holds Hkv heads of slot_cap[s] positions each
-// (slot_cap is a multiple of 32).
-//   V of one head: [pos][d], row-major.
-//   K of one head: blocks of 32 positions; inside a block the 8-element pieces of the head vector
-//   are stored piece-major: element (pos, j) lies at k_elem_offset(pos, j, d).  A wave reading
-//   piece c of 32 consecutive positions touches 512 contiguous bytes, and that is exactly the row
-//   operand of a 32x32x16 MFMA (lane = position, 8 consecutive k), so scores are computed from K
-//   as it lies in memory.
+// (slot_cap is a multiple of 32).  Both K and V of one head are stored in blocks of 32 positions,
+// each block (32 * d elements, contiguous) in the order in which a 32x32x16 MFMA wants its row
+// operand, so attention reads the cache as it lies in memory with 16-byte loads:
+//   K (row = position, contraction over d): the 8-element pieces of the head vector are stored
+//   piece-major: element (pos, j) lies at k_elem_offset(pos, j, d).  A wave reading piece c of 32
+//   consecutive positions touches 512 contiguous bytes.
+//   V (row = head dim, contraction over positions): 8 positions form a piece, pieces are stored
+//   [piece][j][8].  The 8 positions of piece w = 2t + h are {16t + 4h + 0..3, 16t + 8 + 4h + 0..3}:
+//   exactly the positions that lane half h of a 32x32 accumulator holds for k-step t, so softmax
+//   probabilities go from the score accumulators into the second MFMA without leaving registers.
 __host__ __device__ inline size_t k_piece_offset(int pos, int piece, int d) {
     return (size_t)(pos >> 5) * 32 * d + (((size_t)piece * 32 + (pos & 31)) << 3);
 }
 __host__ __device__ inline size_t k_elem_offset(int pos, int j, int d) { return k_piece_offset(pos, j >> 3, d) + (j & 7); }
+__host__ __device__ inline size_t v_elem_offset(int pos, int j, int d) {
+    const int p = pos & 31, t = p >> 4, g = p & 15, h = (g >> 2) & 1, e = (g & 3) + ((g >> 3) << 2);
+    return (size_t)(pos >> 5) * 32 * d + (((size_t)(2 * t + h) * d + j) << 3) + e;
+}
 
 struct KvView {
     act_t* k;                 // layer's K part

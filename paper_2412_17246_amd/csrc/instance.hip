@@ -336,6 +336,9 @@ int bz_create(const bz_config* cfg, bz_instance** out) {
             }
         HIP_TRY_C(hipMemcpy(I->wsp + I->ws.rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice));
     }
+    // attention multiplies V of masked positions by zero instead of skipping it: the cache must never
+    // hold non-finite bit patterns, so it starts out cleared (also when the caller brought the arena)
+    HIP_TRY_C(hipMemset(I->kv, 0, I->sz.kv_arena_bytes));
     HIP_TRY_C(hipMemset(I->wsp + I->ws.slot_off, 0, (size_t)cfg->max_seqs * sizeof(int32_t)));
     HIP_TRY_C(hipMemset(I->wsp + I->ws.slot_cap, 0, (size_t)cfg->max_seqs * sizeof(int32_t)));
     HIP_TRY_C(hipDeviceSynchronize());

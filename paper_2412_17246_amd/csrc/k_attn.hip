@@ -1,9 +1,14 @@
 // Causal attention over the KV cache: a tiled MFMA kernel for sequences with several new tokens
 // (prefill) and a split-KV kernel plus fixed-order combine for sequences with one (decode).
 //
-// Cache layout per (layer, slot, kv head): V[pos][d]; K in blocks of 32 positions stored piece-major
-// (k_piece_offset), which is the MFMA row-operand order.  Query head h reads kv head h / (Hq/Hkv).  A query at absolute position p sees keys 0..p.  Scores are scaled by
-// 1/sqrt(d); softmax is evaluated in base 2 (scores pre-multiplied by log2 e).
+// Cache layout per (layer, slot, kv head): blocks of 32 positions, K piece-major (k_elem_offset), V
+// in pieces of 8 positions (v_elem_offset): both are the row-operand order of the 32x32x16 MFMA.
+// Query head h reads kv head h / (Hq/Hkv).  A query at absolute position p sees keys 0..p.  Scores
+// are scaled by 1/sqrt(d); softmax is evaluated in base 2 (scores pre-multiplied by log2 e).
+//
+// V is multiplied by probability 0 (not skipped) at masked positions of a partly visible block, so
+// cache memory must hold finite values everywhere: the arena is cleared when an instance is created
+// and only finite values are ever written by the kernels.
 #include "common.h"
 
 namespace bz {
@@ -11,23 +16,36 @@ namespace bz {
 constexpr float kLog2e = 1.4426950408889634f;
 
 #ifndef BZ_FP32_DEBUG
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// 2^x by the hardware instruction alone (results below the normal range flush to zero, which is
+// what a softmax weight that small should be anyway)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ---------------------------------------------------------------------------------------------
 // Prefill.  One workgroup = 128 query rows of one (sequence, head); each of its 4 waves owns 32
 // rows.  The wave computes S^T = K * Q^T with 32x32x16 MFMAs, so that a lane (and its partner
 // lane + 32) holds all scores of ONE query row: row max / sum need a single cross-lane exchange
 // and the running rescale of O^T is a per-lane scalar.  P^T feeds the second MFMA (O^T = V^T *
 // P^T) straight from registers: the accumulator layout of S^T is a permutation of the B-operand
-// layout along the contraction index, and V^T is read from LDS with the same permutation.
+// layout along the contraction index, and the V cache stores its pieces in that permuted order.
+//
+// A KV tile is 64 positions = two cache blocks of K and two of V, each block contiguous in the
+// cache in exactly the order the MFMAs read it, so a tile is moved global -> LDS by the DMA path
+// (no registers), double-buffered: tile i+1 is in flight while tile i is multiplied.
 // ---------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out,
-                                                           BatchView bv, KvView kv, int Hq, float scale_log2) {
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ out,
+                                                              BatchView bv, KvView kv, int Hq, float scale_log2) {
     constexpr int BQ = kPrefillTileQ, BK = 64;
-    constexpr int VROW = BK + 8;     // padded LDS rows (elements)
-    constexpr int DB = D / 32;       // 32-wide blocks of the head dim
-    constexpr int KS = D / 16;       // MFMA k-steps over the head dim
-    __shared__ __attribute__((aligned(16))) bf16 Ks[BK * D];      // two 32-position blocks, piece-major as in the cache
-    __shared__ __attribute__((aligned(16))) bf16 Vt[D * VROW];
+    constexpr int DB = D / 32;           // 32-wide blocks of the head dim
+    constexpr int KS = D / 16;           // MFMA k-steps over the head dim
+    constexpr int BLK = 32 * D;          // elements per cache block
+    constexpr int NL = D / 32;           // 1 KiB DMA loads per wave per tile, for K and again for V
+    constexpr int STAGE = 4 * BLK;       // elements per stage: K tile (2 blocks) then V tile (2 blocks)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* smem = reinterpret_cast<bf16*>(smem_raw);
 
     const int item = blockIdx.x, h = blockIdx.y;
     const int s = bv.prefill_items[2 * item], qt = bv.prefill_items[2 * item + 1];
@@ -44,11 +62,38 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restric
     const int nqkv = (Hq + 2 * Hkv) * D;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int lq = lane & 31, lh = lane >> 5;
     const int qi = qt * BQ + wave * 32 + lq;
     const bool valid = qi < qlen;
     const int qic = valid ? qi : qlen - 1;
     const int qpos = before + qic;
+
+    const int last_q = ((qt * BQ + BQ < qlen) ? qt * BQ + BQ : qlen) - 1;
+    const int kv_end = before + last_q + 1;                 // keys 0..kv_end-1 are visible to this tile
+    const int ntiles = (kv_end + BK - 1) / BK;
+    const int last_blk = (kv_end - 1) >> 5;
+    int wq_first = qt * BQ + wave * 32, wq_last = wq_first + 31;
+    if (wq_last > qlen - 1) wq_last = qlen - 1;
+    if (wq_first > qlen - 1) wq_first = qlen - 1;
+    const int wave_max_pos = before + wq_last, wave_min_pos = before + wq_first;
+
+    // tile -> LDS: wave w moves 1 KiB pieces w*NL .. w*NL+NL-1 of the K tile and of the V tile.  A
+    // block past the last visible one is replaced by the last visible block (its scores are masked).
+    auto issue = [&](int tile, int stage) {
+        bf16* st = smem + stage * STAGE;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int piece = wave_u * NL + j;               // 512 elements each
+            const int blk = piece / (BLK / 512), off = (piece % (BLK / 512)) * 512;
+            int kb = tile * 2 + blk;
+            if (kb > last_blk) kb = last_blk;
+            const size_t src = (size_t)kb * BLK + off + lane * 8;
+            __builtin_amdgcn_global_load_lds((gptr_t)(Kc + src), (lptr_t)(st + piece * 512), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(Vc + src), (lptr_t)(st + 2 * BLK + piece * 512), 16, 0, 0);
+        }
+    };
+    issue(0, 0);
 
     bf16x8 qf[KS];
     {
@@ -57,50 +102,21 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restric
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
     }
 
-    const int last_q = ((qt * BQ + BQ < qlen) ? qt * BQ + BQ : qlen) - 1;
-    const int kv_end = before + last_q + 1;                 // keys 0..kv_end-1 are visible to this tile
-    const int ntiles = (kv_end + BK - 1) / BK;
-    int wq_last = qt * BQ + wave * 32 + 31;
-    if (wq_last > qlen - 1) wq_last = qlen - 1;
-    const int wave_max_pos = before + wq_last;
-
     f32x16 o[DB];
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[b][r] = 0.f;
-    float m = -INFINITY, l = 0.f;
+    float m = -INFINITY, l = 0.f;           // running max (already scaled) and sum of this lane's query row
 
     for (int tile = 0; tile < ntiles; ++tile) {
         const int kbase = tile * BK;
-        __syncthreads();                                     // all waves are done with the previous tile
-        {   // K tile: two 32-position blocks copied as they lie in the cache (a block past the last
-            // visible key is replaced by the last visible block; its scores are masked anyway)
-            constexpr int VPB = 32 * D / 8;                  // 16-byte vectors per block
-#pragma unroll
-            for (int p = 0; p < 2 * VPB / 256; ++p) {
-                const int v = tid + p * 256;
-                const int blk = v / VPB, off = v % VPB;
-                int kb = (kbase >> 5) + blk;
-                if (kb > ((kv_end - 1) >> 5)) kb = (kv_end - 1) >> 5;
-                *reinterpret_cast<uint4*>(&Ks[v * 8]) =
-                    *reinterpret_cast<const uint4*>(Kc + (size_t)kb * 32 * D + off * 8);
-            }
-        }
-        {   // V tile, transposed into Vt[d][kv]
-            constexpr int CH = D / 8;
-#pragma unroll
-            for (int p = 0; p < CH / 4; ++p) {
-                const int kr = tid & 63, c = (tid >> 6) + 4 * p;
-                int kp = kbase + kr;
-                if (kp > kv_end - 1) kp = kv_end - 1;
-                const bf16x8 v = *reinterpret_cast<const bf16x8*>(Vc + (size_t)kp * D + c * 8);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * VROW + kr] = v[e];
-            }
-        }
-        __syncthreads();
+        __builtin_amdgcn_s_waitcnt(0x0070);                  // own pieces of this tile landed, own LDS reads done
+        __syncthreads();                                     // everyone's pieces landed; the other stage is free
+        if (tile + 1 < ntiles) issue(tile + 1, (tile + 1) & 1);
         if (kbase <= wave_max_pos) {                         // wave-uniform: tile not fully masked for this wave
+            const bf16* Ks = smem + (tile & 1) * STAGE;
+            const bf16* Vs = Ks + 2 * BLK;
             f32x16 sacc[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -108,39 +124,46 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restric
                 for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[kb * 32 * D + ((ks * 2 + lh) * 32 + lq) * 8]);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[kb * BLK + ((ks * 2 + lh) * 32 + lq) * 8]);
                     sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
                 }
             }
-            float mx = m;
+            if (kbase + BK - 1 > wave_min_pos) {             // wave-uniform: the diagonal crosses this tile
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int kvi = kbase + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                        if (kvi > qpos) sacc[kb][r] = -INFINITY;
+                    }
+            }
+            float mx = -INFINITY;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kvi = kbase + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    float sc = sacc[kb][r] * scale_log2;
-                    if (kvi > qpos) sc = -INFINITY;
-                    sacc[kb][r] = sc;
-                    mx = fmaxf(mx, sc);
-                }
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+            mx = fmaxf(m, mx * scale_log2);                  // scale > 0: max commutes with it
             mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            const float alpha = exp2f(m - mx);               // m = -inf on the first tile -> 0
+            if (__builtin_amdgcn_ballot_w64(mx != m) != 0) { // some row's max moved: rescale (wave-uniform)
+                const float alpha = fast_exp2(m - mx);       // m = -inf on the first tile -> 0
+                l *= alpha;
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
+                m = mx;
+            }
             float rs = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float p = exp2f(sacc[kb][r] - mx);
+                    const float p = fast_exp2(fmaf(sacc[kb][r], scale_log2, -mx));
                     sacc[kb][r] = p;
                     rs += p;
                 }
             rs += __shfl_xor(rs, 32, kWave);
-            l = l * alpha + rs;
-            m = mx;
-#pragma unroll
-            for (int b = 0; b < DB; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
+            l += rs;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 bf16x8 pf;
@@ -148,12 +171,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restric
                 for (int e = 0; e < 8; ++e) pf[e] = (bf16)sacc[t >> 1][8 * (t & 1) + e];
 #pragma unroll
                 for (int b = 0; b < DB; ++b) {
-                    const bf16* vp = &Vt[(b * 32 + lq) * VROW + t * 16 + 4 * lh];
-                    const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vp);
-                    const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vp + 8);
-                    bf16x8 vf;
-                    vf[0] = v0[0]; vf[1] = v0[1]; vf[2] = v0[2]; vf[3] = v0[3];
-                    vf[4] = v1[0]; vf[5] = v1[1]; vf[6] = v1[2]; vf[7] = v1[3];
+                    const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
+                        &Vs[(t >> 1) * BLK + ((2 * (t & 1) + lh) * D + b * 32 + lq) * 8]);
                     o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[b], 0, 0, 0);
                 }
             }
@@ -175,16 +194,26 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16* __restric
     }
 }
 
+template <int D>
+static void launch_prefill_d(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,
+                             hipStream_t st) {
+    constexpr int kLds = 2 * 4 * 32 * D * (int)sizeof(bf16);     // two stages of (K tile + V tile)
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_kernel<D>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        attr_set = true;
+    }
+    const float scale_log2 = kLog2e / sqrtf((float)D);
+    hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(bv.n_prefill_items, Hq), dim3(256), kLds, st, qkv, out, bv, kv, Hq,
+                       scale_log2);
+}
+
 void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,
                          hipStream_t st) {
     if (bv.n_prefill_items <= 0) return;
-    const float scale_log2 = kLog2e / sqrtf((float)kv.d);
-    const dim3 grid(bv.n_prefill_items, Hq);
-    if (kv.d == 128) {
-        hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, dim3(256), 0, st, qkv, out, bv, kv, Hq, scale_log2);
-    } else {
-        hipLaunchKernelGGL(attn_prefill_kernel<64>, grid, dim3(256), 0, st, qkv, out, bv, kv, Hq, scale_log2);
-    }
+    if (kv.d == 128) launch_prefill_d<128>(qkv, out, bv, kv, Hq, st);
+    else launch_prefill_d<64>(qkv, out, bv, kv, Hq, st);
 }
 
 #else  // BZ_FP32_DEBUG
@@ -226,7 +255,7 @@ __global__ __launch_bounds__(64) void attn_naive_kernel(const float* __restrict_
     __syncthreads();
     for (int e = lane; e < D; e += 64) {
         float a = 0.f;
-        for (int j = 0; j <= pos; ++j) a = fmaf(sc[j], Vc[(size_t)j * D + e], a);
+        for (int j = 0; j <= pos; ++j) a = fmaf(sc[j], Vc[v_elem_offset(j, e, D)], a);
         out[(size_t)t * Hq * D + h * D + e] = a / sum;
     }
 }
@@ -249,25 +278,27 @@ void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, cons
 // ---------------------------------------------------------------------------------------------
 // Decode.  Grid (chunk, kv head, decode sequence).  A workgroup handles kDecodeChunk = 256 cached
 // positions of one kv head for all G = Hq/Hkv query heads that share it: every K and V byte is
-// read from HBM once.  Scores: one lane per position (the lane walks its K row in 16-byte steps).
-// PV: D/8 lanes per V row, so a wave reads whole rows with 16-byte loads.  Each workgroup writes
-// an unnormalised partial (o, running max, sum) per head; the combine kernel folds the chunks of
-// a sequence in increasing chunk order, so the result does not depend on scheduling.
+// read from HBM once.  Each of the 4 waves owns 64 positions and runs on its own until the four
+// partial results are merged.  Each workgroup writes an unnormalised partial (o, running max, sum)
+// per head; the combine kernel folds the chunks of a sequence in increasing chunk order, so the
+// result does not depend on scheduling.
 // ---------------------------------------------------------------------------------------------
-template <int D, int G>
-__global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restrict__ qkv, float* __restrict__ partial,
-                                                          BatchView bv, KvView kv, int Hq, float scale_log2) {
+constexpr int kDecodeMaxG = 8;
+
+#ifndef BZ_FP32_DEBUG
+// Both products run on the matrix cores with the cache as the row operand, read from global
+// memory straight into the instructions (a lane's 16 bytes are one operand register pair):
+//   S^T[pos, g] = K[pos, :] . q[g, :]     q fills G of the 32 columns, the rest are zero;
+//   O^T[j, g]   = V^T[j, pos] . P^T[pos, g]   P^T goes from the score accumulators to the column
+//   operand inside the registers (the V cache is stored in the matching position order).
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restrict__ qkv, float* __restrict__ partial,
+                                                             BatchView bv, KvView kv, int Hq, int G, float scale_log2) {
     constexpr int CH = kDecodeChunk;
-    constexpr int LPR = D / 8;            // lanes per V row
-    constexpr int RPI = 64 / LPR;         // V rows per wave load
-    constexpr int NSTEP = 64 / RPI;       // V loads per lane for the wave's 64 positions
-    __shared__ float ps[4][G][64];
-    __shared__ float wmx[4][G];
-    __shared__ float wsum[4][G];
-    __shared__ float osh[4][G][D];
-#ifdef BZ_FP32_DEBUG
-    __shared__ float qs[G][D];
-#endif
+    constexpr int KS = D / 16, DB = D / 32, BLK = 32 * D;
+    __shared__ float wmx[4][kDecodeMaxG];
+    __shared__ float wsum[4][kDecodeMaxG];
+    __shared__ float osh[4][kDecodeMaxG][D];
 
     const int chunk = blockIdx.x, kvh = blockIdx.y, di = blockIdx.z;
     const int s = bv.decode_seqs[di];
@@ -278,33 +309,41 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
     const int slot = bv.seq_slot[s];
     const int Hkv = kv.Hkv, cap = kv.slot_cap[slot];
     const size_t head_base = (size_t)kv.slot_off[slot] * Hkv * D + (size_t)kvh * cap * D;
-    const act_t* Kc = kv.k + head_base;
-    const act_t* Vc = kv.v + head_base;
+    const bf16* Kc = kv.k + head_base;
+    const bf16* Vc = kv.v + head_base;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const act_t* q = qkv + (size_t)t * (Hq + 2 * Hkv) * D + (size_t)kvh * G * D;    // G query heads, contiguous
+    const int lq = lane & 31, lh = lane >> 5;
+    const bf16* q = qkv + (size_t)t * (Hq + 2 * Hkv) * D + (size_t)kvh * G * D;    // G query heads, contiguous
 
-    // Each wave owns 64 positions and runs on its own: no workgroup barrier until the four partial
-    // results are merged.  Rows past the end are read from the last valid row (so all loads are
-    // unconditional and in bounds) and get probability zero.
     const int w0 = c0 + wave * 64;
-    const int sub = lane / LPR, dv = (lane % LPR) * 8;
-    raw8_act vv[NSTEP];
+    if (w0 < len) {                                          // wave-uniform
+        const int last_blk = (len - 1) >> 5;
+        // a block past the end is replaced by the last valid one (loads stay unconditional and in
+        // bounds); its positions get probability zero
+        size_t boff[2];
 #pragma unroll
-    for (int stp = 0; stp < NSTEP; ++stp) {           // V rows first: they stay in flight under the score math
-        int vp = w0 + stp * RPI + sub;
-        if (vp > len - 1) vp = len - 1;
-        load_raw8(Vc + (size_t)vp * D + dv, vv[stp]);
-    }
-
-#ifndef BZ_FP32_DEBUG
-    // Scores on the matrix cores: S^T[pos, g] = K[pos, :] . q[g, :].  A K row is the MFMA's row
-    // operand exactly as it lies in memory (lane = position, 16 bytes per k-step), so it goes from
-    // global memory straight into the instruction; q fills G of the 32 columns, the rest are zero.
-    {
-        const int lq = lane & 31, lh = lane >> 5;
-        bf16x8 qf[D / 16];
+        for (int rb = 0; rb < 2; ++rb) {
+            int kb = (w0 >> 5) + rb;
+            if (kb > last_blk) kb = last_blk;
+            boff[rb] = (size_t)kb * BLK;
+        }
+        bf16x8 kf[2][KS], vf[2][2][DB];
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[rb][ks] = *reinterpret_cast<const bf16x8*>(Kc + boff[rb] + ((ks * 2 + lh) * 32 + lq) * 8);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    vf[rb][tt][db] =
+                        *reinterpret_cast<const bf16x8*>(Vc + boff[rb] + ((2 * tt + lh) * D + db * 32 + lq) * 8);
+        bf16x8 qf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
             if (lq < G) qf[ks] = *reinterpret_cast<const bf16x8*>(q + lq * D + ks * 16 + lh * 8);
             else
 #pragma unroll
@@ -313,17 +352,11 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
         f32x16 sacc[2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            int kb = (w0 >> 5) + rb;                         // 32-position block; past the end: the last valid one
-            if (kb > ((len - 1) >> 5)) kb = (len - 1) >> 5;
-            const bf16* kr = Kc + (size_t)kb * 32 * D + (lh * 32 + lq) * 8;
-            bf16x8 kf[D / 16];
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(kr + ks * 2 * 32 * 8);
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[rb][r] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks)
-                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc[rb], 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks)
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[rb][ks], qf[ks], sacc[rb], 0, 0, 0);
         }
         // lane (g = lane%32, h = lane/32) holds positions rb*32 + 8*(r/4) + 4h + r%4 of head g
         float m = -INFINITY;
@@ -336,31 +369,105 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
                 sacc[rb][r] = sg;
                 m = fmaxf(m, sg);
             }
-        m = fmaxf(m, __shfl_xor(m, 32, kWave));
+        m = fmaxf(m, __shfl_xor(m, 32, kWave));              // finite: position w0 is valid
         float l = 0.f;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = (sacc[rb][r] == -INFINITY) ? 0.f : exp2f(sacc[rb][r] - m);
+                const float p = exp2f(sacc[rb][r] - m);
                 sacc[rb][r] = p;
                 l += p;
             }
         l += __shfl_xor(l, 32, kWave);
+        f32x16 oacc[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                bf16x8 pf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[e] = (bf16)sacc[rb][8 * tt + e];
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[rb][tt][db], pf, oacc[db], 0, 0, 0);
+            }
         if (lq < G) {
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4)
-                    *reinterpret_cast<float4*>(&ps[wave][lq][rb * 32 + 8 * r4 + 4 * lh]) =
-                        make_float4(sacc[rb][4 * r4], sacc[rb][4 * r4 + 1], sacc[rb][4 * r4 + 2], sacc[rb][4 * r4 + 3]);
+                    *reinterpret_cast<float4*>(&osh[wave][lq][db * 32 + 8 * r4 + 4 * lh]) =
+                        make_float4(oacc[db][4 * r4], oacc[db][4 * r4 + 1], oacc[db][4 * r4 + 2], oacc[db][4 * r4 + 3]);
             if (lh == 0) {
                 wmx[wave][lq] = m;
                 wsum[wave][lq] = l;
             }
         }
+    } else {                                                 // nothing cached in this wave's range
+        for (int i = lane; i < G * D; i += 64) osh[wave][i / D][i % D] = 0.f;
+        if (lane < G) {
+            wmx[wave][lane] = -INFINITY;
+            wsum[wave][lane] = 0.f;
+        }
     }
+    __syncthreads();
+    // merge the four waves in wave order
+    const int PS = decode_partial_stride(D);
+    for (int i = tid; i < G * D; i += 256) {
+        const int g = i / D, dd = i - g * D;
+        const float M = fmaxf(fmaxf(wmx[0][g], wmx[1][g]), fmaxf(wmx[2][g], wmx[3][g]));
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc = fmaf(osh[w][g][dd], exp2f(wmx[w][g] - M), acc);
+        partial[(((size_t)di * Hq + kvh * G + g) * bv.decode_chunks + chunk) * PS + dd] = acc;
+    }
+    if (tid < G) {
+        const int g = tid;
+        const float M = fmaxf(fmaxf(wmx[0][g], wmx[1][g]), fmaxf(wmx[2][g], wmx[3][g]));
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) L = fmaf(wsum[w][g], exp2f(wmx[w][g] - M), L);
+        float* pp = partial + (((size_t)di * Hq + kvh * G + g) * bv.decode_chunks + chunk) * PS;
+        pp[D] = M;
+        pp[D + 1] = L;
+    }
+}
+
 #else
+// fp32 debug build: scores with one lane per position, PV with D/8 lanes per position, on the VALU.
+template <int D, int G>
+__global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restrict__ qkv, float* __restrict__ partial,
+                                                          BatchView bv, KvView kv, int Hq, int, float scale_log2) {
+    constexpr int CH = kDecodeChunk;
+    constexpr int LPR = D / 8;            // lanes per position in the PV product
+    constexpr int RPI = 64 / LPR;         // positions per wave step
+    constexpr int NSTEP = 64 / RPI;       // steps for the wave's 64 positions
+    __shared__ float ps[4][G][64];
+    __shared__ float wmx[4][G];
+    __shared__ float wsum[4][G];
+    __shared__ float osh[4][G][D];
+    __shared__ float qs[G][D];
+
+    const int chunk = blockIdx.x, kvh = blockIdx.y, di = blockIdx.z;
+    const int s = bv.decode_seqs[di];
+    const int len = bv.kv_before[s] + 1;
+    const int c0 = chunk * CH;
+    if (c0 >= len) return;
+    const int t = bv.q_start[s];
+    const int slot = bv.seq_slot[s];
+    const int Hkv = kv.Hkv, cap = kv.slot_cap[slot];
+    const size_t head_base = (size_t)kv.slot_off[slot] * Hkv * D + (size_t)kvh * cap * D;
+    const float* Kc = kv.k + head_base;
+    const float* Vc = kv.v + head_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* q = qkv + (size_t)t * (Hq + 2 * Hkv) * D + (size_t)kvh * G * D;
+    const int w0 = c0 + wave * 64;
+    const int sub = lane / LPR, dv = (lane % LPR) * 8;
     {
         for (int i = tid; i < G * D / 8; i += 256) {
             float v[8];
@@ -396,22 +503,22 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
             }
         }
     }
-#endif
 
     float o[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[g][e] = 0.f;
-#pragma unroll
     for (int stp = 0; stp < NSTEP; ++stp) {
         const int prow = stp * RPI + sub;
+        int vp = w0 + prow;
+        if (vp > len - 1) vp = len - 1;                  // probability zero there
         float vf[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vf[e] = raw_get(vv[stp], e);
+        for (int e = 0; e < 8; ++e) vf[e] = Vc[v_elem_offset(vp, dv + e, D)];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const float pw = ps[wave][g][prow];       // written by this wave only
+            const float pw = ps[wave][g][prow];           // written by this wave only
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[g][e] = fmaf(pw, vf[e], o[g][e]);
         }
@@ -454,22 +561,46 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const act_t* __restric
     }
 }
 
+#endif
+
+// One workgroup per (decode sequence, head), one thread per head-dim index.  Chunks are folded in
+// increasing order, sixteen per batch: all loads of a batch are independent (an index past the end
+// re-reads the last chunk; its value is not added), so a sequence of up to 4096 positions costs one
+// memory round trip.  Across batches the running (max, numerator, denominator) is rescaled.
 template <int D>
 __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ partial, act_t* __restrict__ out,
                                                          BatchView bv, int Hq) {
+    constexpr int NB = 16;
     const int di = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
     const int s = bv.decode_seqs[di];
     const int len = bv.kv_before[s] + 1;
     const int nch = (len + kDecodeChunk - 1) / kDecodeChunk;
     const int PS = decode_partial_stride(D);
     const float* base = partial + ((size_t)di * Hq + h) * bv.decode_chunks * PS;
-    float M = -INFINITY;
-    for (int c = 0; c < nch; ++c) M = fmaxf(M, base[c * PS + D]);
-    float num = 0.f, den = 0.f;
-    for (int c = 0; c < nch; ++c) {
-        const float w = exp2f(base[c * PS + D] - M);
-        num = fmaf(base[c * PS + dd], w, num);
-        den = fmaf(base[c * PS + D + 1], w, den);
+    float M = -INFINITY, num = 0.f, den = 0.f;
+    for (int c0 = 0; c0 < nch; c0 += NB) {
+        float mv[NB], ov[NB], lv[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const float* pc = base + ((c0 + u < nch) ? c0 + u : nch - 1) * PS;
+            mv[u] = pc[D];
+            ov[u] = pc[dd];
+            lv[u] = pc[D + 1];
+        }
+        float Mb = M;
+#pragma unroll
+        for (int u = 0; u < NB; ++u) Mb = fmaxf(Mb, mv[u]);
+        const float keep = exp2f(M - Mb);                // 0 for the first batch (M = -inf)
+        num *= keep;
+        den *= keep;
+        M = Mb;
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+            if (c0 + u < nch) {
+                const float w = exp2f(mv[u] - M);
+                num = fmaf(ov[u], w, num);
+                den = fmaf(lv[u], w, den);
+            }
     }
     act_t r;
     from_f32(r, num / den);
@@ -481,12 +612,17 @@ static void launch_decode_d(const act_t* qkv, act_t* out, float* partial, const 
                             int Hq, hipStream_t st) {
     const float scale_log2 = kLog2e / sqrtf((float)D);
     const dim3 grid(bv.decode_chunks, kv.Hkv, bv.n_decode);
-    switch (Hq / kv.Hkv) {
-        case 1: hipLaunchKernelGGL((attn_decode_kernel<D, 1>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
-        case 2: hipLaunchKernelGGL((attn_decode_kernel<D, 2>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
-        case 4: hipLaunchKernelGGL((attn_decode_kernel<D, 4>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
-        default: hipLaunchKernelGGL((attn_decode_kernel<D, 8>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, scale_log2); break;
+    const int G = Hq / kv.Hkv;                      // 1, 2, 4 or 8: checked when the instance is created
+#ifndef BZ_FP32_DEBUG
+    hipLaunchKernelGGL(attn_decode_kernel<D>, grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, G, scale_log2);
+#else
+    switch (G) {
+        case 1: hipLaunchKernelGGL((attn_decode_kernel<D, 1>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, G, scale_log2); break;
+        case 2: hipLaunchKernelGGL((attn_decode_kernel<D, 2>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, G, scale_log2); break;
+        case 4: hipLaunchKernelGGL((attn_decode_kernel<D, 4>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, G, scale_log2); break;
+        default: hipLaunchKernelGGL((attn_decode_kernel<D, 8>), grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, G, scale_log2); break;
     }
+#endif
     hipLaunchKernelGGL(attn_combine_kernel<D>, dim3(bv.n_decode, Hq), dim3(D), 0, st, partial, out, bv, Hq);
 }
 

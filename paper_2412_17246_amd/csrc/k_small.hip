@@ -97,23 +97,67 @@ void launch_reduce_residual_rmsnorm(act_t* x, const float* partial, int ksplit, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Rotary embedding + KV append.  One workgroup per token.  Q is rotated in place inside the
-// packed [T, (Hq+2Hkv)*d] projection output; K is rotated and written to the cache; V is copied
-// to the cache.  Pairs are (j, j + d/2); the cos/sin table is [max_seq_len][d/2][2] floats built
-// on the host in float64.
+// Rotary embedding + KV append.  Q is rotated in place inside the packed [T, (Hq+2Hkv)*d]
+// projection output; K is rotated and written to the cache; V is copied to the cache.  Pairs are
+// (j, j + d/2); the cos/sin table is [max_seq_len][d/2][2] floats built on the host in float64.
+//
+// Workgroups [n_vblocks, n_vblocks + T) handle one token each (rotation, K write).  The V cache
+// keeps 8 positions of one head-dim index in 16 contiguous bytes, so V of a token alone is a
+// scatter of single elements: the token's workgroup does that only for positions whose aligned
+// group of 16 positions is not written completely by this batch (single-token sequences, ragged
+// ends).  Complete groups are written by workgroups [0, n_vblocks): block (prefill item, sub, h)
+// gathers the 8 positions of one piece for every (kv head, j) and stores them as one vector.
 // ---------------------------------------------------------------------------------------------
 template <bool REDUCE>
 __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qkv, const float* __restrict__ partial,
                                                           int ksplit, const float* __restrict__ tab, BatchView bv,
-                                                          KvView kv, int Hq) {
-    const int t = blockIdx.x;
-    const int s = bv.token_seq[t];
-    const int pos = bv.kv_before[s] + (t - bv.q_start[s]);
-    const int slot = bv.seq_slot[s];
+                                                          KvView kv, int Hq, int n_vblocks) {
     const int d = kv.d, Hkv = kv.Hkv, half = d >> 1;
+    const int nqkv = (Hq + 2 * Hkv) * d;
+    if ((int)blockIdx.x < n_vblocks) {
+        const int item = blockIdx.x >> 4, sub = (blockIdx.x >> 1) & 7, h = blockIdx.x & 1;
+        const int s = bv.prefill_items[2 * item], qt = bv.prefill_items[2 * item + 1];
+        const int q0 = bv.q_start[s];
+        const int before = bv.kv_before[s];
+        const int end = before + (bv.q_start[s + 1] - q0);
+        const int grp = ((before + 15) >> 4) + qt * 8 + sub;      // aligned group of 16 positions
+        if (grp * 16 + 16 > end) return;
+        const int slot = bv.seq_slot[s];
+        const int cap = kv.slot_cap[slot];
+        const size_t slot_base = (size_t)kv.slot_off[slot] * Hkv * d;
+        const int p0 = grp * 16 + 4 * h;                          // the piece holds p0 + {0..3, 8..11}
+        const act_t* src = qkv + (size_t)(q0 + (p0 - before)) * nqkv + (size_t)(Hq + Hkv) * d;
+        const size_t piece_off = (size_t)(p0 >> 5) * 32 * d + (size_t)(2 * ((p0 >> 4) & 1) + h) * d * 8;
+        for (int u = threadIdx.x; u < Hkv * d; u += blockDim.x) {
+            const int kvh = u / d, j = u - kvh * d;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const size_t idx = (size_t)((e & 3) + 8 * (e >> 2)) * nqkv + u;
+                if (REDUCE) {
+                    const size_t off = (size_t)(src - qkv) + idx;
+                    float a = 0.f;
+                    for (int k = 0; k < ksplit; ++k) a += partial[k * ((size_t)bv.T * nqkv) + off];
+                    act_t r;
+                    from_f32(r, a);
+                    v[e] = to_f32(r);
+                } else {
+                    v[e] = to_f32(src[idx]);
+                }
+            }
+            store8(kv.v + slot_base + (size_t)kvh * cap * d + piece_off + (size_t)j * 8, v);
+        }
+        return;
+    }
+    const int t = blockIdx.x - n_vblocks;
+    const int s = bv.token_seq[t];
+    const int before = bv.kv_before[s];
+    const int pos = before + (t - bv.q_start[s]);
+    const int end = before + (bv.q_start[s + 1] - bv.q_start[s]);
+    const bool v_by_group = (pos & ~15) >= before && (pos & ~15) + 16 <= end;
+    const int slot = bv.seq_slot[s];
     const int cap = kv.slot_cap[slot];
     const size_t slot_base = (size_t)kv.slot_off[slot] * Hkv * d;
-    const int nqkv = (Hq + 2 * Hkv) * d;
     act_t* row = qkv + (size_t)t * nqkv;
     const float* cs = tab + (size_t)pos * d;   // [half][2]
     // REDUCE: the projection output is still split-K partial sums; fold them in slice order and round
@@ -134,9 +178,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
     };
     const int units_per_head = half >> 3;      // 8 pairs per unit
     const int rot_units = (Hq + Hkv) * units_per_head;
-    const int v_units = Hkv * (d >> 3);
-    for (int u = threadIdx.x; u < rot_units + v_units; u += blockDim.x) {
-        if (u < rot_units) {
+    for (int u = threadIdx.x; u < rot_units; u += blockDim.x) {
+        {
             const int head = u / units_per_head;          // 0..Hq-1 query heads, then key heads
             const int j0 = (u - head * units_per_head) * 8;
             act_t* hp = row + head * d;
@@ -158,13 +201,29 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
                 store8(dst + k_piece_offset(pos, j0 >> 3, d), o_lo);
                 store8(dst + k_piece_offset(pos, (half + j0) >> 3, d), o_hi);
             }
-        } else {
-            const int w = u - rot_units;
-            const int kvh = w / (d >> 3);
-            const int j0 = (w - kvh * (d >> 3)) * 8;
-            float v[8];
-            fetch8((Hq + Hkv + kvh) * d + j0, v);
-            store8(kv.v + slot_base + ((size_t)kvh * cap + pos) * d + j0, v);
+        }
+    }
+    if (!v_by_group) {                                  // workgroup-uniform
+        // single elements: the row is fetched in vectors and handed over through LDS so that consecutive
+        // lanes store consecutive j, i.e. cache addresses 16 bytes apart
+        constexpr int kPass = 2048;
+        __shared__ act_t vst[kPass];
+        const int vcol = (Hq + Hkv) * d, nv = Hkv * d;
+        for (int base = 0; base < nv; base += kPass) {
+            const int cnt = nv - base < kPass ? nv - base : kPass;
+            const int u8 = threadIdx.x * 8;
+            if (u8 < cnt) {
+                float v[8];
+                fetch8(vcol + base + u8, v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) from_f32(vst[u8 + e], v[e]);
+            }
+            __syncthreads();
+            for (int u = threadIdx.x; u < cnt; u += blockDim.x) {
+                const int kvh = (base + u) / d, j = (base + u) - kvh * d;
+                kv.v[slot_base + (size_t)kvh * cap * d + v_elem_offset(pos, j, d)] = vst[u];
+            }
+            __syncthreads();
         }
     }
 }
@@ -172,18 +231,24 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
 void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, const KvView& kv, int Hq,
                         hipStream_t st) {
     if (bv.T <= 0) return;
-    hipLaunchKernelGGL(rope_append_kernel<false>, dim3(bv.T), dim3(256), 0, st, qkv, nullptr, 0, rope_tab, bv, kv, Hq);
+    const int nvb = bv.n_prefill_items * 16;
+    hipLaunchKernelGGL(rope_append_kernel<false>, dim3(nvb + bv.T), dim3(256), 0, st, qkv, nullptr, 0, rope_tab, bv, kv,
+                       Hq, nvb);
 }
 
 void launch_rope_append_reduce(act_t* qkv, const float* partial, int ksplit, const float* rope_tab,
                                const BatchView& bv, const KvView& kv, int Hq, hipStream_t st) {
     if (bv.T <= 0) return;
-    hipLaunchKernelGGL(rope_append_kernel<true>, dim3(bv.T), dim3(256), 0, st, qkv, partial, ksplit, rope_tab, bv, kv,
-                       Hq);
+    const int nvb = bv.n_prefill_items * 16;
+    hipLaunchKernelGGL(rope_append_kernel<true>, dim3(nvb + bv.T), dim3(256), 0, st, qkv, partial, ksplit, rope_tab, bv,
+                       kv, Hq, nvb);
 }
 
 // ---------------------------------------------------------------------------------------------
 // KV scatter/gather between token-major [n, Hkv, d] buffers and the cache layout of one slot.
+// K: one thread per 8 head-dim elements of a token (16 bytes on both sides).  V: one thread per
+// (piece of 8 positions, kv head, j), 16 bytes on the cache side; pieces that the range
+// [pos0, pos0 + n) covers only partly are handled element by element.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void kv_scatter_kernel(const act_t* __restrict__ src_k,
                                                          const act_t* __restrict__ src_v, KvView kv, int slot,
@@ -193,28 +258,57 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(const act_t* __restrict
     const int cap = kv.slot_cap[slot];
     const size_t slot_base = (size_t)kv.slot_off[slot] * Hkv * d;
     const int vec_per_tok = Hkv * (d >> 3);
-    const size_t total = (size_t)n * vec_per_tok;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+    const size_t k_total = (size_t)n * vec_per_tok;
+    const int piece0 = (pos0 >> 5) * 4;                          // first piece of the first block touched
+    const int n_pieces = (((pos0 + n - 1) >> 5) + 1) * 4 - piece0;
+    const size_t v_total = (size_t)n_pieces * Hkv * d;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < k_total + v_total;
          i += (size_t)gridDim.x * blockDim.x) {
-        const int tok = (int)(i / vec_per_tok);
-        const int w = (int)(i - (size_t)tok * vec_per_tok);
-        const int kvh = w / (d >> 3);
-        const int j0 = (w - kvh * (d >> 3)) * 8;
-        const size_t lin = (size_t)tok * Hkv * d + (size_t)kvh * d + j0;
-        const size_t head = slot_base + (size_t)kvh * cap * d;
-        const size_t cac_v = head + (size_t)(pos0 + tok) * d + j0;
-        const size_t cac_k = head + k_piece_offset(pos0 + tok, j0 >> 3, d);
-        float a[8], b[8];
-        if (to_cache) {
-            load8(src_k + lin, a);
-            load8(src_v + lin, b);
-            store8(kv.k + cac_k, a);
-            store8(kv.v + cac_v, b);
+        if (i < k_total) {
+            const int tok = (int)(i / vec_per_tok);
+            const int w = (int)(i - (size_t)tok * vec_per_tok);
+            const int kvh = w / (d >> 3);
+            const int j0 = (w - kvh * (d >> 3)) * 8;
+            const size_t lin = (size_t)tok * Hkv * d + (size_t)kvh * d + j0;
+            const size_t cac_k = slot_base + (size_t)kvh * cap * d + k_piece_offset(pos0 + tok, j0 >> 3, d);
+            float a[8];
+            if (to_cache) {
+                load8(src_k + lin, a);
+                store8(kv.k + cac_k, a);
+            } else {
+                load8(kv.k + cac_k, a);
+                store8(dst_k + lin, a);
+            }
         } else {
-            load8(kv.k + cac_k, a);
-            load8(kv.v + cac_v, b);
-            store8(dst_k + lin, a);
-            store8(dst_v + lin, b);
+            const size_t vi = i - k_total;
+            const int u = (int)(vi % ((size_t)Hkv * d));          // kvh * d + j: consecutive lanes, consecutive j
+            const int piece = piece0 + (int)(vi / ((size_t)Hkv * d));
+            const int kvh = u / d, j = u - kvh * d;
+            const int w = piece & 3;                              // piece 2t + h of its block
+            const int pbase = (piece >> 2) * 32 + 16 * (w >> 1) + 4 * (w & 1);
+            act_t* cv = kv.v + slot_base + (size_t)kvh * cap * d + (size_t)(piece >> 2) * 32 * d + ((size_t)w * d + j) * 8;
+            const bool whole = pbase >= pos0 && pbase + 11 < pos0 + n;
+            if (to_cache) {
+                if (whole) {
+                    float b[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        b[e] = to_f32(src_v[(size_t)(pbase + (e & 3) + 8 * (e >> 2) - pos0) * Hkv * d + u]);
+                    store8(cv, b);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int p = pbase + (e & 3) + 8 * (e >> 2);
+                        if (p >= pos0 && p < pos0 + n) cv[e] = src_v[(size_t)(p - pos0) * Hkv * d + u];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int p = pbase + (e & 3) + 8 * (e >> 2);
+                    if (p >= pos0 && p < pos0 + n) dst_v[(size_t)(p - pos0) * Hkv * d + u] = cv[e];
+                }
+            }
         }
     }
 }
@@ -222,7 +316,8 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(const act_t* __restrict
 void launch_kv_scatter(const act_t* src_k, const act_t* src_v, const KvView& kv, int slot, int pos0, int n,
                        bool to_cache, act_t* dst_k, act_t* dst_v, hipStream_t st) {
     if (n <= 0) return;
-    const size_t total = (size_t)n * kv.Hkv * (kv.d >> 3);
+    const size_t n_pieces = (size_t)((((pos0 + n - 1) >> 5) + 1) - (pos0 >> 5)) * 4;
+    const size_t total = (size_t)n * kv.Hkv * (kv.d >> 3) + n_pieces * kv.Hkv * kv.d;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(kv_scatter_kernel, dim3(blocks), dim3(256), 0, st, src_k, src_v, kv, slot, pos0, n,
