@@ -443,12 +443,17 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 constexpr int kSkStage = (64 + 64) * kBK * (int)sizeof(bf16);    // 16384
 constexpr int kSkStages = 4;
 
+// GU (gate/up projection): a tile is 32 gate features (weight rows n0..n0+31) and the 32 matching up
+// features (rows N + n0..), so that with a single k-slice the workgroup holds both factors of
+// silu(gate) * up and writes the activation itself (C != nullptr) instead of partial sums.
+template <bool GU>
 __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
-                                                             float* __restrict__ partial, int M, int Nrows, int K,
-                                                             int n_tiles, int kt_per_split) {
+                                                             float* __restrict__ partial, bf16* __restrict__ C, int M,
+                                                             int Nrows, int K, int n_tiles, int kt_per_split) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
     const int tile_n = blockIdx.x % n_tiles, split = blockIdx.x / n_tiles;
-    const int n0 = tile_n * 64;
+    const int n0 = tile_n * (GU ? 32 : 64);
+    const int Nh = Nrows >> 1;                        // GU: features per factor
     const int nk = K / kBK;
     const int kt0 = split * kt_per_split;
     const int kt1 = (kt0 + kt_per_split < nk) ? kt0 + kt_per_split : nk;
@@ -469,8 +474,15 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restr
         int xr = row;
         if (xr > M - 1) xr = M - 1;
         x_src[j] = ((uint32_t)xr * (uint32_t)K + c * 8) * 2u;
-        int wr = n0 + row;
-        if (wr > Nrows - 1) wr = Nrows - 1;
+        int wr;
+        if (GU) {
+            int f = n0 + (row & 31);
+            if (f > Nh - 1) f = Nh - 1;
+            wr = (row >> 5) * Nh + f;
+        } else {
+            wr = n0 + row;
+            if (wr > Nrows - 1) wr = Nrows - 1;
+        }
         w_src[j] = ((uint32_t)wr * (uint32_t)K + c * 8) * 2u;
     }
     auto issue = [&](int kt, int stage) {
@@ -513,14 +525,42 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restr
         }
     }
 
-    // partial[split][m][n]: lane holds token wt*32 + lane%32, features 8g + 4*(lane/32) + 0..3
+    // lane holds token wt*32 + lane%32 and, of its wave's 32 features, 8g + 4*(lane/32) + 0..3
     const int m = wt * 32 + lrow;
-    if (m < M) {
+    if (GU && C != nullptr) {
+        // the up-factor waves hand their accumulators to the gate-factor waves (same lane, same
+        // token half) through LDS, which is free once everyone has read the last stage
+        float* ex = reinterpret_cast<float*>(smem_raw);
+        __syncthreads();
+        if (wf == 1) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ex[(wt * 16 + r) * 64 + lane] = acc[r];
+        }
+        __syncthreads();
+        if (wf == 0 && m < M) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int nn = n0 + 8 * g + 4 * lk;
+                if (nn < Nh) {
+                    bf16x4 w4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float o = acc[4 * g + e], u = ex[(wt * 16 + 4 * g + e) * 64 + lane];
+                        w4[e] = (bf16)(o / (1.0f + __expf(-o)) * u);
+                    }
+                    *reinterpret_cast<bf16x4*>(C + (size_t)m * Nh + nn) = w4;
+                }
+            }
+        }
+        return;
+    }
+    if (m < M) {                                       // partial[split][m][n]
         float* prow = partial + ((size_t)split * M + m) * Nrows;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int nn = n0 + wf * 32 + 8 * g + 4 * lk;
-            if (nn < Nrows)
+            const int f = n0 + (GU ? 0 : wf * 32) + 8 * g + 4 * lk;
+            const int nn = GU ? wf * Nh + f : f;
+            if (f < (GU ? Nh : Nrows))
                 *reinterpret_cast<float4*>(prow + nn) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
         }
     }
@@ -594,31 +634,45 @@ static bool skinny_applies(int mode, int M, int N, int K, const float* ws, size_
 
 // Split-K partial sums only: partial[ksplit][M][Nrows] (Nrows = 2N in SwiGLU mode).  The caller
 // folds the slices in slice order, either with gemm_skinny_epilogue or fused into the next kernel.
-static int launch_skinny_partial(int mode, const bf16* a, const bf16* w, int M, int N, int K, float* ws, hipStream_t st) {
+// `c` (gate/up mode only): where the activation goes when one k-slice covers K; then the return value is 0
+// and no partial sums are written.
+static int launch_skinny_partial(int mode, const bf16* a, const bf16* w, bf16* c, int M, int N, int K, float* ws,
+                                 hipStream_t st) {
     const SkinnyPlan p = skinny_plan(M, N, K, mode);
     const int Nrows = (mode == 2) ? 2 * N : N;
     constexpr int LDS = kSkStages * kSkStage;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemm_skinny_kernel, dim3(p.n_tiles * p.ksplit), dim3(256), LDS, st, a, w, ws, M, Nrows, K,
-                       p.n_tiles, p.kt_per_split);
+    const dim3 grid(p.n_tiles * p.ksplit);
+    if (mode == 2) {
+        bf16* direct = (p.ksplit == 1) ? c : nullptr;
+        hipLaunchKernelGGL(gemm_skinny_kernel<true>, grid, dim3(256), LDS, st, a, w, ws, direct, M, Nrows, K, p.n_tiles,
+                           p.kt_per_split);
+        if (direct) return 0;
+    } else {
+        hipLaunchKernelGGL(gemm_skinny_kernel<false>, grid, dim3(256), LDS, st, a, w, ws, nullptr, M, Nrows, K, p.n_tiles,
+                           p.kt_per_split);
+    }
     return p.ksplit;
 }
 
 int launch_gemm_partial(int mode, const act_t* a, const bf16* w, int M, int N, int K, float* ws, size_t ws_bytes,
                         hipStream_t st) {
     if (M <= 0 || N <= 0 || !skinny_applies(mode, M, N, K, ws, ws_bytes)) return 0;
-    return launch_skinny_partial(mode, a, w, M, N, K, ws, st);
+    return launch_skinny_partial(mode, a, w, nullptr, M, N, K, ws, st);
 }
 
 template <int MODE>
 static void launch_skinny(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
                           hipStream_t st) {
-    const int ksplit = launch_skinny_partial(MODE, a, w, M, N, K, ws, st);
+    const int ksplit = launch_skinny_partial(MODE, a, w, c, M, N, K, ws, st);
+    if (ksplit == 0) return;                          // the kernel wrote the result itself
     const int Nrows = (MODE == 2) ? 2 * N : N;
     const int threads = M * (N >> 2);
     hipLaunchKernelGGL(gemm_skinny_epilogue<MODE>, dim3((threads + 255) / 256), dim3(256), 0, st, ws, r, c, M, N, Nrows,

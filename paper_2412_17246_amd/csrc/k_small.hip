@@ -178,6 +178,12 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
     };
     const int units_per_head = half >> 3;      // 8 pairs per unit
     const int rot_units = (Hq + Hkv) * units_per_head;
+    // V of a token that is stored element by element: first vector requested before the rotation so
+    // that both round trips to memory overlap
+    constexpr int kPass = 2048;
+    const int vcol = (Hq + Hkv) * d, nv = Hkv * d;
+    float vpre[8];
+    if (!v_by_group && (int)threadIdx.x * 8 < nv) fetch8(vcol + threadIdx.x * 8, vpre);
     for (int u = threadIdx.x; u < rot_units; u += blockDim.x) {
         {
             const int head = u / units_per_head;          // 0..Hq-1 query heads, then key heads
@@ -206,17 +212,14 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
     if (!v_by_group) {                                  // workgroup-uniform
         // single elements: the row is fetched in vectors and handed over through LDS so that consecutive
         // lanes store consecutive j, i.e. cache addresses 16 bytes apart
-        constexpr int kPass = 2048;
         __shared__ act_t vst[kPass];
-        const int vcol = (Hq + Hkv) * d, nv = Hkv * d;
         for (int base = 0; base < nv; base += kPass) {
             const int cnt = nv - base < kPass ? nv - base : kPass;
             const int u8 = threadIdx.x * 8;
             if (u8 < cnt) {
-                float v[8];
-                fetch8(vcol + base + u8, v);
+                if (base > 0) fetch8(vcol + base + u8, vpre);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) from_f32(vst[u8 + e], v[e]);
+                for (int e = 0; e < 8; ++e) from_f32(vst[u8 + e], vpre[e]);
             }
             __syncthreads();
             for (int u = threadIdx.x; u < cnt; u += blockDim.x) {
