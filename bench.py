@@ -178,6 +178,11 @@ def run_prefill_stream(args, torch, Instance):
     gen.manual_seed(shape.seed)
     n_blobs = min(shape.L, args.distinct_blobs) if args.distinct_blobs else shape.L
     blobs = [gen_layer_blob_gpu(torch, inst, shape, gen) for _ in range(n_blobs)]
+    shard_views = []
+    if args.shards > 1:
+        step = -(-inst.layer_bytes // args.shards // 256) * 256
+        for b in blobs:
+            shard_views.append([(b[o:min(o + step, inst.layer_bytes)], o) for o in range(0, inst.layer_bytes, step)])
     x0 = torch.from_numpy(W.hidden_bits(shape, T, step=0).view(np.int16).copy()).view(torch.bfloat16).cuda()
     x = torch.empty_like(x0)
     batch = inst.batch(q_start, list(range(B)), [0] * B)
@@ -186,7 +191,10 @@ def run_prefill_stream(args, torch, Instance):
     def one_step():                       # scale start -> first token; returns once everything is enqueued
         inst.reset_clock()
         for l in range(shape.L):
-            inst.load_layer(l, blobs[l % n_blobs])
+            if args.shards > 1:           # the same bytes as k parallel shards (section 5.1, sharded transfer)
+                inst.load_layer_sharded(l, shard_views[l % n_blobs])
+            else:
+                inst.load_layer(l, blobs[l % n_blobs])
         inst.run_layers(0, shape.L, batch, x)
 
     def reset():
@@ -229,7 +237,8 @@ def run_prefill_stream(args, torch, Instance):
                       f"{shape.name}-shaped decoder, {shape.L} layers streamed from pinned host memory while a packed "
                       f"prefill batch of {B} requests ({T} tokens) runs behind the frontier",
                       {"shape": shape.name, "layers": shape.L, "requests": B, "tokens": T,
-                       "lengths": [int(v) for v in lens], "distinct_host_blobs": n_blobs})
+                       "lengths": [int(v) for v in lens], "distinct_host_blobs": n_blobs,
+                       "shards_per_layer": max(1, args.shards)})
     out.update({
         "ttft_ms": ms_per_step,
         "ingest_GBps": shape.L * inst.layer_bytes / (float(np.median(ingest_ms)) * 1e-3) / 1e9,
@@ -526,6 +535,7 @@ def main() -> int:
     ap.add_argument("--requests", type=int, default=8)
     ap.add_argument("--fixed-len", type=int, default=0, help="prefill_stream: every request has this many tokens")
     ap.add_argument("--distinct-blobs", type=int, default=0, help="prefill_stream: feed layer i from pinned blob i mod m")
+    ap.add_argument("--shards", type=int, default=1, help="prefill_stream: ingest every layer as this many parallel shards")
     ap.add_argument("--split", type=int, default=0, help="decode: also run a live split at this layer and compare bits")
     ap.add_argument("--chunk-mib", type=int, default=0, help="ingest chunk size in MiB (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

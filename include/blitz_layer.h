@@ -175,6 +175,23 @@ int bz_sync(bz_instance* inst);                  /* waits for both streams */
 int bz_load_layer(bz_instance* inst, int layer, const void* host, size_t n);
 /* Same, from a device buffer (a resident peer's copy: one hop of section 5.1's forwarding chain). */
 int bz_load_layer_from_device(bz_instance* inst, int layer, const void* dev, size_t n);
+/* Parallel sharded transfer (section 5.1, "parallel sharded parameter transfer from multiple
+ * sources"): the layer's bytes arrive as n_shards <= BZ_MAX_SHARDS contiguous pieces, each from its
+ * own source buffer, spread over two extra copy streams so that transfers from different sources
+ * overlap; the layer's event fires when all of them have landed (the point at which the paper's
+ * all-gather has finished).
+ * Shard j copies `bytes` bytes from `src` (pinned host memory, or device memory if src_is_device) to
+ * byte `offset` of the layer; the shards, in any order, must cover [0, layer_bytes) exactly once
+ * (BZ_EINVAL otherwise).  Sources are borrowed until the layer is resident.  BZ_EBUSY as above. */
+#define BZ_MAX_SHARDS 16
+typedef struct bz_shard {
+    const void* src;
+    size_t      offset;
+    size_t      bytes;
+    int32_t     src_is_device;
+    int32_t     reserved_;
+} bz_shard;
+int bz_load_layer_sharded(bz_instance* inst, int layer, const bz_shard* shards, int n_shards);
 /* Forgets layer i (waits for both streams first); it must be loaded again before it can run. */
 int bz_unload_layer(bz_instance* inst, int layer);
 

@@ -65,6 +65,14 @@ class bz_stats(C.Structure):
                 ("layer_launches", C.c_uint64), ("frontier", C.c_int32), ("reserved", C.c_int32)]
 
 
+class bz_shard(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("offset", C.c_size_t), ("bytes", C.c_size_t), ("src_is_device", C.c_int32),
+                ("reserved_", C.c_int32)]
+
+
+BZ_MAX_SHARDS = 16
+
+
 class bz_zz_event(C.Structure):
     _fields_ = [("request", C.c_int32), ("instance", C.c_int32), ("layer_a", C.c_int32), ("layer_b", C.c_int32),
                 ("frontier", C.c_int32), ("t_ms", C.c_float)]
@@ -93,6 +101,7 @@ SIGNATURES = {
     "bz_sync": (C.c_int, [_P]),
     "bz_load_layer": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
     "bz_load_layer_from_device": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
+    "bz_load_layer_sharded": (C.c_int, [_P, C.c_int, C.POINTER(bz_shard), C.c_int]),
     "bz_unload_layer": (C.c_int, [_P, C.c_int]),
     "bz_frontier": (C.c_int, [_P]),
     "bz_layer_ready": (C.c_int, [_P, C.c_int]),
@@ -288,6 +297,15 @@ class Instance:
         self._keep.append(dev)
         self._check(self.lib.bz_load_layer_from_device(self.handle, layer, _ptr(dev), dev.numel()),
                     "bz_load_layer_from_device")
+
+    def load_layer_sharded(self, layer: int, shards) -> None:
+        """shards: sequence of (source tensor, byte offset in the layer); each source supplies its
+        whole length.  Host tensors must be pinned."""
+        arr = (bz_shard * len(shards))()
+        for j, (t, off) in enumerate(shards):
+            self._keep.append(t)
+            arr[j] = bz_shard(_ptr(t), int(off), t.numel() * t.element_size(), 1 if t.is_cuda else 0, 0)
+        self._check(self.lib.bz_load_layer_sharded(self.handle, layer, arr, len(shards)), "bz_load_layer_sharded")
 
     def unload_layer(self, layer: int) -> None:
         self._check(self.lib.bz_unload_layer(self.handle, layer), "bz_unload_layer")

@@ -66,4 +66,6 @@ struct bz_instance {
     bool prof_on = false;
     std::vector<bz::ProfRec> prof;
     std::vector<hipEvent_t> ev_pool;
+    std::vector<hipStream_t> shard_streams;      // created on first sharded load
+    std::vector<hipEvent_t> shard_events;
 };

@@ -1,5 +1,6 @@
 // Host side of the C ABI: instance state, layer ingest with per-layer events, the frontier,
 // KV slots, batches, the per-layer kernel sequence, boundary hand-off, counters.
+#include <algorithm>
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
@@ -265,6 +266,8 @@ int bz_destroy(bz_instance* I) {
         if (I->copy) (void)hipStreamSynchronize(I->copy);
         for (hipEvent_t e : I->ev) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : I->ev_pool) (void)hipEventDestroy(e);
+        for (hipStream_t q : I->shard_streams) { (void)hipStreamSynchronize(q); (void)hipStreamDestroy(q); }
+        for (hipEvent_t e : I->shard_events) (void)hipEventDestroy(e);
         for (auto& r : I->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
         if (I->t0) (void)hipEventDestroy(I->t0);
         if (I->own_weights && I->weights) (void)hipFree(I->weights);
@@ -361,6 +364,62 @@ int bz_load_layer(bz_instance* I, int layer, const void* host, size_t n) {
 
 int bz_load_layer_from_device(bz_instance* I, int layer, const void* dev, size_t n) {
     return enqueue_copy(I, layer, dev, n, hipMemcpyDeviceToDevice);
+}
+
+int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int n_shards) {
+    if (!I || !shards || n_shards < 1 || n_shards > BZ_MAX_SHARDS) return BZ_EINVAL;
+    if (layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
+    // the shards must tile [0, layer_bytes) exactly: sort indices by offset, then walk
+    int order[BZ_MAX_SHARDS];
+    for (int j = 0; j < n_shards; ++j) order[j] = j;
+    std::sort(order, order + n_shards, [&](int a, int b) { return shards[a].offset < shards[b].offset; });
+    size_t at = 0;
+    for (int k = 0; k < n_shards; ++k) {
+        const bz_shard& sh = shards[order[k]];
+        if (!sh.src || sh.bytes == 0 || sh.offset != at) return BZ_EINVAL;
+        at += sh.bytes;
+        if (at > I->sz.layer_bytes) return BZ_EINVAL;
+    }
+    if (at != I->sz.layer_bytes) return BZ_EINVAL;
+    if (I->state[layer] != kNone) return BZ_EBUSY;
+    if (I->dry) return BZ_ESTATE;
+    // Shards alternate over a small fixed set of extra streams: a process has few hardware queues
+    // (four here), and a stream beyond them shares a queue with the compute stream, whose kernels
+    // then wait behind copies.
+    constexpr int kShardStreams = 2;
+    const int n_streams = n_shards < kShardStreams ? n_shards : kShardStreams;
+    while ((int)I->shard_streams.size() < n_streams) {
+        hipStream_t q = nullptr;
+        hipEvent_t e = nullptr;
+        HIP_TRY(hipStreamCreateWithFlags(&q, hipStreamNonBlocking));
+        I->shard_streams.push_back(q);
+        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        I->shard_events.push_back(e);
+    }
+    if (!I->clock_started) {
+        HIP_TRY(hipEventRecord(I->t0, I->copy));
+        I->clock_started = true;
+    }
+    const size_t chunk = I->cfg.chunk_bytes > 0 ? (size_t)I->cfg.chunk_bytes : ((size_t)32 << 20);
+    unsigned char* dst = layer_ptr(I, layer);
+    for (int j = 0; j < n_shards; ++j) {
+        const bz_shard& sh = shards[j];
+        const unsigned char* s = static_cast<const unsigned char*>(sh.src);
+        const hipMemcpyKind kind = sh.src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        for (size_t off = 0; off < sh.bytes; off += chunk) {
+            const size_t m = sh.bytes - off < chunk ? sh.bytes - off : chunk;
+            HIP_TRY(hipMemcpyAsync(dst + sh.offset + off, s + off, m, kind, I->shard_streams[j % n_streams]));
+        }
+    }
+    for (int q = 0; q < n_streams; ++q) {
+        HIP_TRY(hipEventRecord(I->shard_events[q], I->shard_streams[q]));
+        HIP_TRY(hipStreamWaitEvent(I->copy, I->shard_events[q], 0));
+    }
+    HIP_TRY(hipEventRecord(I->ev[layer], I->copy));      // fires when every shard has landed
+    I->state[layer] = kLoading;
+    I->stats.bytes_ingested += I->sz.layer_bytes;
+    I->stats.layers_requested += 1;
+    return BZ_OK;
 }
 
 int bz_unload_layer(bz_instance* I, int layer) {

@@ -32,20 +32,32 @@ __device__ __forceinline__ void reduce8(const float* __restrict__ partial, int k
 }
 
 // REDUCE: the row of x is first completed as x + (sum of split-K slices), rounded and stored; the
-// norm then works on the stored values, so its result is bit-identical to a separate norm kernel.
+// norm then works on the rounded values, so its result is bit-identical to a separate norm kernel.
+// The first kKeep vectors of a thread (rows up to 8 * kKeep * THREADS elements: every supported
+// shape) stay in registers between the two passes together with their gains, so the row makes one
+// trip from memory.
 template <int THREADS, bool REDUCE>
 __global__ __launch_bounds__(THREADS) void rmsnorm_kernel(act_t* __restrict__ x, const float* __restrict__ partial,
                                                           int ksplit, int T, const bf16* __restrict__ gain,
                                                           act_t* __restrict__ y, int H, float eps) {
     constexpr int NW = THREADS / kWave;
+    constexpr int kKeep = 4;
     __shared__ float red[NW];
     const int row = blockIdx.x;
     act_t* xr = x + (size_t)row * H;
     act_t* yr = y + (size_t)row * H;
     const int nvec = H >> 3;
+    float keep[kKeep][8];
+    raw8_bf16 gk[kKeep];
+    if (gain != nullptr) {
+#pragma unroll
+        for (int c = 0; c < kKeep; ++c) {
+            const int i = threadIdx.x + c * THREADS;
+            if (i < nvec) load_raw8(gain + i * 8, gk[c]);
+        }
+    }
     float ss = 0.f;
-    for (int i = threadIdx.x; i < nvec; i += THREADS) {
-        float v[8];
+    auto first_pass = [&](int i, float (&v)[8]) {
         load8(xr + i * 8, v);
         if (REDUCE) {
             float s[8];
@@ -53,10 +65,24 @@ __global__ __launch_bounds__(THREADS) void rmsnorm_kernel(act_t* __restrict__ x,
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = s[e] + v[e];
             store8(xr + i * 8, v);
-            load8(xr + i * 8, v);                  // the rounded values (this thread's own store)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {              // continue with the values as stored
+                act_t r;
+                from_f32(r, v[e]);
+                v[e] = to_f32(r);
+            }
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss = fmaf(v[e], v[e], ss);
+    };
+#pragma unroll
+    for (int c = 0; c < kKeep; ++c) {
+        const int i = threadIdx.x + c * THREADS;
+        if (i < nvec) first_pass(i, keep[c]);
+    }
+    for (int i = threadIdx.x + kKeep * THREADS; i < nvec; i += THREADS) {
+        float v[8];
+        first_pass(i, v);
     }
     if (gain == nullptr) return;
     ss = wave_sum(ss);
@@ -66,7 +92,17 @@ __global__ __launch_bounds__(THREADS) void rmsnorm_kernel(act_t* __restrict__ x,
 #pragma unroll
     for (int w = 0; w < NW; ++w) tot += red[w];
     const float rstd = 1.0f / sqrtf(tot / (float)H + eps);
-    for (int i = threadIdx.x; i < nvec; i += THREADS) {
+#pragma unroll
+    for (int c = 0; c < kKeep; ++c) {
+        const int i = threadIdx.x + c * THREADS;
+        if (i < nvec) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (keep[c][e] * rstd) * raw_get(gk[c], e);
+            store8(yr + i * 8, o);
+        }
+    }
+    for (int i = threadIdx.x + kKeep * THREADS; i < nvec; i += THREADS) {
         float v[8], g[8];
         load8(xr + i * 8, v);
         load8(gain + i * 8, g);

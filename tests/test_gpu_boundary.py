@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 import workloads as W
+from paper_2412_17246_amd import binding as B
 from tests import _util as U
 
 pytestmark = pytest.mark.gpu
@@ -45,6 +46,60 @@ def test_device_resident_source_and_reload(torch):
     blob2 = blob[::-1].copy()
     inst.load_layer(0, inst.pinned_blob(blob2))        # the same slot can be loaded again after unload
     assert np.array_equal(inst.readback_layer(0), blob2)
+    inst.close()
+
+
+@pytest.mark.parametrize("n_shards", [1, 3, 4, 16])
+def test_sharded_ingest_is_byte_exact_and_ready_only_when_all_shards_landed(torch, n_shards):
+    """Section 5.1, parallel sharded transfer: uneven shards, given out of order, from a mix of pinned
+    host and device sources, on one stream each; the layer's bytes equal the whole blob; a following
+    unsharded layer still completes; the frontier covers both."""
+    inst = U.make_instance(TINY, max_seqs=1, max_seq_len=32, max_tokens=8, kv_tokens=32, chunk_bytes=64 << 10)
+    n = inst.layer_bytes
+    rng = np.random.default_rng(40 + n_shards)
+    blob = rng.integers(0, 256, n, dtype=np.uint8)
+    cuts = np.sort(rng.choice(np.arange(1, n), size=n_shards - 1, replace=False)) if n_shards > 1 else np.array([], int)
+    edges = [0] + [int(c) for c in cuts] + [n]
+    shards = []
+    for j in range(n_shards):
+        piece = blob[edges[j]:edges[j + 1]]
+        src = torch.from_numpy(piece.copy()).cuda() if j % 2 else inst.pinned_blob(piece)
+        shards.append((src, edges[j]))
+    torch.cuda.synchronize()
+    shards = shards[::-1]                                  # any order
+    inst.load_layer_sharded(0, shards)
+    blob1 = blob[::-1].copy()
+    inst.load_layer(1, inst.pinned_blob(blob1))
+    inst.wait_layer(1)
+    assert inst.frontier() == 2
+    assert np.array_equal(inst.readback_layer(0), blob)
+    assert np.array_equal(inst.readback_layer(1), blob1)
+    assert inst.stats()["bytes_ingested"] == 2 * n
+    inst.close()
+
+
+def test_sharded_ingest_rejects_gaps_overlaps_and_wrong_totals(torch):
+    inst = U.make_instance(TINY, max_seqs=1, max_seq_len=32, max_tokens=8, kv_tokens=32)
+    n = inst.layer_bytes
+    half = inst.pinned_blob(np.zeros(n // 2, np.uint8))
+    rest = inst.pinned_blob(np.zeros(n - n // 2, np.uint8))
+    for bad in ([(half, 0)],                                # too short
+                [(half, 0), (rest, n // 2 + 16)],           # gap (and runs past the end)
+                [(half, 0), (rest, n // 2 - 16)],           # overlap
+                [(half, 0), (rest, n // 2), (half, 0)],     # covered twice
+                [(half, 16), (rest, n // 2 + 16)]):         # does not start at 0
+        with pytest.raises(B.BzError) as e:
+            inst.load_layer_sharded(0, bad)
+        assert e.value.name == "BZ_EINVAL"
+    with pytest.raises(B.BzError) as e:
+        inst.load_layer_sharded(0, [(half, 0)] * (B.BZ_MAX_SHARDS + 1))
+    assert e.value.name == "BZ_EINVAL"
+    assert inst.frontier() == 0
+    inst.load_layer_sharded(0, [(half, 0), (rest, n // 2)])
+    with pytest.raises(B.BzError) as e:
+        inst.load_layer_sharded(0, [(half, 0), (rest, n // 2)])
+    assert e.value.name == "BZ_EBUSY"
+    inst.wait_layer(0)
     inst.close()
 
 
