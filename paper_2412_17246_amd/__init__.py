@@ -20,4 +20,5 @@ from .binding import (  # noqa: F401
     op_gemm,
     op_gemm_workspace_bytes,
     op_rmsnorm,
+    plan_generate,
 )

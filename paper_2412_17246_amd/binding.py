@@ -73,6 +73,19 @@ class bz_shard(C.Structure):
 BZ_MAX_SHARDS = 16
 
 
+class bz_plan_node(C.Structure):
+    _fields_ = [("id", C.c_int32), ("n_gpus", C.c_int32), ("leaf", C.c_int32), ("role", C.c_int32),
+                ("out_busy", C.c_int32), ("reserved_", C.c_int32), ("gpu_bw", C.c_double)]
+
+
+class bz_plan_hop(C.Structure):
+    _fields_ = [("chain", C.c_int32), ("src", C.c_int32), ("dst", C.c_int32), ("is_tail", C.c_int32),
+                ("bw", C.c_double), ("ready_s", C.c_double)]
+
+
+BZ_PLAN_SOURCE, BZ_PLAN_SPARE, BZ_PLAN_OTHER = 0, 1, 2
+
+
 class bz_zz_event(C.Structure):
     _fields_ = [("request", C.c_int32), ("instance", C.c_int32), ("layer_a", C.c_int32), ("layer_b", C.c_int32),
                 ("frontier", C.c_int32), ("t_ms", C.c_float)]
@@ -102,6 +115,9 @@ SIGNATURES = {
     "bz_load_layer": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
     "bz_load_layer_from_device": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
     "bz_load_layer_sharded": (C.c_int, [_P, C.c_int, C.POINTER(bz_shard), C.c_int]),
+    "bz_plan_generate": (C.c_int, [C.POINTER(bz_plan_node), C.c_int, C.c_int, C.c_double, C.c_int, C.c_double,
+                                   C.POINTER(bz_plan_hop), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int),
+                                   C.POINTER(C.c_int)]),
     "bz_unload_layer": (C.c_int, [_P, C.c_int]),
     "bz_frontier": (C.c_int, [_P]),
     "bz_layer_ready": (C.c_int, [_P, C.c_int]),
@@ -397,6 +413,35 @@ def zz_simulate(policy: int, n_layers: int, n_requests: int, load_time: float, s
     if rc:
         raise BzError(rc, "bz_zz_simulate")
     return list(T), list(fin)
+
+
+def plan_generate(nodes, n_targets: int, oversub: float, n_layers: int, layer_bytes: float,
+                  fp32_debug: bool = False) -> dict:
+    """Scale-plan generation.  nodes: sequence of (id, n_gpus, gpu_bw, leaf, role, out_busy).
+    Returns chains (node ids, root first), per-hop bandwidths, per-target ready times, chain tails and
+    whether a source with a busy outgoing link had to be used."""
+    lib = load_library(fp32_debug)
+    arr = (bz_plan_node * max(1, len(nodes)))()
+    for i, (nid, gpus, bw, leaf, role, busy) in enumerate(nodes):
+        arr[i] = bz_plan_node(int(nid), int(gpus), int(leaf), int(role), 1 if busy else 0, 0, float(bw))
+    hops = (bz_plan_hop * max(1, n_targets))()
+    n_hops, n_chains, interferes = C.c_int(), C.c_int(), C.c_int()
+    rc = lib.bz_plan_generate(arr, len(nodes), n_targets, oversub, n_layers, layer_bytes, hops, max(1, n_targets),
+                              C.byref(n_hops), C.byref(n_chains), C.byref(interferes))
+    if rc:
+        raise BzError(rc, "bz_plan_generate")
+    chains = [[] for _ in range(n_chains.value)]
+    hop_bw = [[] for _ in range(n_chains.value)]
+    ready, tails = {}, []
+    for h in hops[:n_hops.value]:
+        if not chains[h.chain]:
+            chains[h.chain].append(h.src)
+        chains[h.chain].append(h.dst)
+        hop_bw[h.chain].append(h.bw)
+        ready[h.dst] = h.ready_s
+        if h.is_tail:
+            tails.append(h.dst)
+    return {"chains": chains, "hop_bw": hop_bw, "ready": ready, "tails": tails, "interferes": bool(interferes.value)}
 
 
 class Scheduler:

@@ -13,7 +13,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
-SOURCES = ["instance.hip", "zigzag.hip", "k_small.hip", "k_gemm.hip", "k_attn.hip"]
+SOURCES = ["instance.hip", "zigzag.hip", "plan.hip", "k_small.hip", "k_gemm.hip", "k_attn.hip"]
 LIB = os.path.join(PKG, "libblitzlayer.so")
 LIB_FP32 = os.path.join(PKG, "libblitzlayer_fp32dbg.so")
 

@@ -20,7 +20,8 @@ def lib(request):
 
 
 def test_every_declared_symbol_is_exported_and_bound(lib):
-    text = open(os.path.join(ROOT, "include", "blitz_layer.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(bz_[a-z0-9_]+)\s*\(", text))
     assert declared, "no declarations found"
@@ -168,3 +169,61 @@ def test_scheduler_decisions_match_the_oracle_in_virtual_time():
     lib = B.load_library()
     assert lib.bz_zz_simulate(5, 3, 3, 1.0, 0.0, (C.c_int32 * 3)(), (C.c_double * 3)()) == -1     # unknown policy
     assert lib.bz_zz_create(None, None, 0, C.byref(C.c_void_p())) == -1
+
+
+def _random_cluster(rng):
+    n = int(rng.integers(2, 14))
+    nodes = []
+    for i in rng.permutation(40)[:n]:
+        role = int(rng.choice([B.BZ_PLAN_SOURCE, B.BZ_PLAN_SPARE, B.BZ_PLAN_SPARE, B.BZ_PLAN_OTHER]))
+        nodes.append((int(i), int(rng.choice([1, 2, 4, 8])), float(rng.choice([12.5e9, 25e9, 50e9])),
+                      int(rng.integers(0, 4)), role, bool(rng.random() < 0.3)))
+    return nodes
+
+
+def test_scale_plan_matches_the_oracle_on_random_clusters():
+    """The C++ planner against the CPU oracle: same chains, same hop bandwidths, same ready times
+    (both evaluate the same float64 expressions), same interference flag and tails."""
+    from oracle import multicast_plan as P
+    rng = np.random.default_rng(5)
+    checked = 0
+    for _ in range(300):
+        nodes = _random_cluster(rng)
+        onodes = [P.Node(id=i, n_gpus=g, gpu_bw=bw, leaf=leaf, role=role, out_busy=busy)
+                  for i, g, bw, leaf, role, busy in nodes]
+        n_spare = sum(1 for n in onodes if n.role == P.SPARE)
+        has_src = any(n.role == P.SOURCE for n in onodes)
+        oversub = float(rng.choice([1.0, 2.0, 4.0]))
+        L, layer = int(rng.integers(1, 40)), float(rng.choice([1.6e6, 4.05e8, 1.7e9]))
+        for n_t in sorted({1, max(1, n_spare // 2), max(1, n_spare)}):
+            if not has_src or n_t > n_spare:
+                with pytest.raises(B.BzError) as e:
+                    B.plan_generate(nodes, n_t, oversub, L, layer)
+                assert e.value.name == "BZ_ECAPACITY"
+                continue
+            want = P.generate(onodes, n_t, oversub)
+            got = B.plan_generate(nodes, n_t, oversub, L, layer)
+            assert got["chains"] == want.chains
+            assert got["hop_bw"] == want.hop_bw
+            assert got["tails"] == want.tails and got["interferes"] == want.interferes
+            assert got["ready"] == P.plan_ready_times(want, L, layer)
+            checked += 1
+    assert checked > 200
+
+
+def test_scale_plan_argument_checks():
+    ok = [(0, 1, 25e9, 0, B.BZ_PLAN_SOURCE, False), (1, 1, 25e9, 0, B.BZ_PLAN_SPARE, False)]
+    assert B.plan_generate(ok, 1, 1.0, 4, 1e6)["chains"] == [[0, 1]]
+    for bad_nodes, args in [
+        (ok, (0, 1.0, 4, 1e6)),                                   # no target asked for
+        (ok, (1, 0.5, 4, 1e6)),                                   # oversubscription below 1
+        (ok, (1, 1.0, 0, 1e6)),                                   # no layers
+        (ok, (1, 1.0, 4, 0.0)),                                   # empty layers
+        ([ok[0], (0, 1, 25e9, 0, B.BZ_PLAN_SPARE, False)], (1, 1.0, 4, 1e6)),      # duplicate id
+        ([ok[0], (1, 0, 25e9, 0, B.BZ_PLAN_SPARE, False)], (1, 1.0, 4, 1e6)),      # node without GPUs
+        ([ok[0], (1, 1, 0.0, 0, B.BZ_PLAN_SPARE, False)], (1, 1.0, 4, 1e6)),       # no bandwidth
+        ([ok[0], (1, 1, 25e9, 0, 7, False)], (1, 1.0, 4, 1e6)),                    # unknown role
+    ]:
+        with pytest.raises(B.BzError) as e:
+            B.plan_generate(bad_nodes, *args)
+        assert e.value.name == "BZ_EINVAL", (bad_nodes, args)
