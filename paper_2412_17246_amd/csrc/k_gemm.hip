@@ -220,19 +220,12 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 // WN = waves along the output-feature dimension: 2 (4 waves, 128x128 per wave) or 4 (8 waves, two per
 // SIMD, 128x64 per wave).
-template <int MODE, int WN>
-__global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
-                                                                const bf16* R, bf16* C, int M, int N, int K,
-                                                                int tiles_m, int tiles_n) {
+// logical tile id -> tile coordinates: groups of 4 tile rows, walked column by column, so that the
+// tiles running together on an XCD share operand rows in its L2
+struct BigTile { int m0, n0; };
+template <int MODE>
+__device__ __forceinline__ BigTile big_tile_of(int pid, int tiles_m, int tiles_n) {
     constexpr int OUT_BN = (MODE == 2) ? 128 : 256;
-    constexpr int NWAVES = 2 * WN;
-    constexpr int NJ = 8 / WN;                 // 32-wide feature blocks per wave (gate+up blocks in SwiGLU mode)
-    constexpr int NCH = 32 / NWAVES;           // 1 KiB chunks of each tile filled by one wave
-    constexpr int NMMA = 4 * NJ;               // MFMAs per k-step
-    constexpr int NFETCH = 4 + NJ;             // LDS operand reads per k-step
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-
-    const int pid = xcd_remap(blockIdx.x, tiles_m * tiles_n);
     constexpr int GROUP = 4;
     const int width = GROUP * tiles_n;
     const int group_id = pid / width;
@@ -240,8 +233,99 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
     const int gsize = (tiles_m - first_m < GROUP) ? (tiles_m - first_m) : GROUP;
     const int tile_m = first_m + (pid % width) % gsize;
     const int tile_n = (pid % width) / gsize;
-    const int m0 = tile_m * 256;
-    const int n0 = tile_n * OUT_BN;
+    return BigTile{tile_m * 256, tile_n * OUT_BN};
+}
+
+// Output of one 32-token block of a wave: lane holds token m and, of each 32-feature block j,
+// features fbase[j] + 8*g + 4*lk + 0..3 (accumulator registers 4g..4g+3).
+// `get(j, x)` returns accumulator register x of block j (a callable, so the caller's registers are read in place).
+template <int MODE, int NJ, class Get>
+__device__ __forceinline__ void big_store_block(Get get, int m, int n0, const int (&fbase)[NJ], int lk,
+                                                const bf16* R, bf16* C, int M, int N) {
+    if (m >= M) return;
+    bf16* crow = C + (size_t)m * N;
+    if (MODE == 2) {
+#pragma unroll
+        for (int j = 0; j < NJ / 2; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + fbase[j] + 8 * g + 4 * lk;
+                if (n < N) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gt = get(j, 4 * g + e), up = get(j + NJ / 2, 4 * g + e);
+                        o[e] = (bf16)(gt / (1.0f + __expf(-gt)) * up);
+                    }
+                    *reinterpret_cast<bf16x4*>(crow + n) = o;
+                }
+            }
+    } else {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + fbase[j] + 8 * g + 4 * lk;
+                if (n < N) {
+                    bf16x4 o;
+                    if (MODE == 1) {
+                        const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (bf16)(get(j, 4 * g + e) + (float)rv[e]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (bf16)get(j, 4 * g + e);
+                    }
+                    *reinterpret_cast<bf16x4*>(crow + n) = o;
+                }
+            }
+    }
+}
+
+template <int MODE, int NJ, int WN>
+__device__ __forceinline__ void big_feature_bases(int wn, int (&fbase)[NJ], int (&wrow)[NJ]) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        int row;       // row of the weight tile (0..127 gate / plain, 128..255 up / plain)
+        if (MODE == 2) row = (j < NJ / 2) ? (wn * (NJ / 2) + j) * 32 : 128 + (wn * (NJ / 2) + (j - NJ / 2)) * 32;
+        else row = (wn * NJ + j) * 32;
+        fbase[j] = (MODE == 2 && j >= NJ / 2) ? row - 128 : row;     // output feature offset inside the tile
+        wrow[j] = row;
+    }
+}
+
+// Tile scheduling.  A launch runs one workgroup per CU at a time, so `tiles` whole tiles take
+// ceil(tiles / 256) rounds and a last round with few tiles wastes most of the chip.  The first
+// n_dp tiles (a multiple of 256) are computed whole by one launch; each of the remaining tiles is
+// cut into `splits` ranges of K, one workgroup each (a second launch of the PARTIAL instantiation,
+// which starts as the first drains), which write fp32 partial tiles to `ws`; a small third kernel
+// adds the partial tiles in range order and applies the epilogue.  The cut is a function of the
+// problem shape only.
+template <int MODE, int WN, bool PARTIAL>
+__global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
+                                                                const bf16* R, bf16* C, int M, int N, int K,
+                                                                int tiles_m, int tiles_n, int n_dp, int splits,
+                                                                float* __restrict__ ws) {
+    constexpr int NWAVES = 2 * WN;
+    constexpr int NJ = 8 / WN;                 // 32-wide feature blocks per wave (gate+up blocks in SwiGLU mode)
+    constexpr int NCH = 32 / NWAVES;           // 1 KiB chunks of each tile filled by one wave
+    constexpr int NMMA = 4 * NJ;               // MFMAs per k-step
+    constexpr int NFETCH = 4 + NJ;             // LDS operand reads per k-step
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+
+    const int nk = K / kBK;
+    int pid, kt0 = 0, kt1 = nk;
+    const int slot = blockIdx.x;                       // PARTIAL: (split tile, K range)
+    if (!PARTIAL) {
+        pid = xcd_remap(blockIdx.x, n_dp);
+    } else {
+        pid = n_dp + slot / splits;
+        const int per = (nk + splits - 1) / splits;
+        kt0 = (slot % splits) * per;
+        kt1 = (kt0 + per < nk) ? kt0 + per : nk;
+    }
+    const BigTile bt = big_tile_of<MODE>(pid, tiles_m, tiles_n);
+    const int m0 = bt.m0, n0 = bt.n0;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -299,13 +383,11 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
     const int sw = swz(lrow);
 #pragma unroll
     for (int i = 0; i < 4; ++i) x_off[i] = (wm * 128 + i * 32 + lrow) * 128;
+    {
+        int wrow[NJ];
+        big_feature_bases<MODE, NJ, WN>(wn, fbase, wrow);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        int row;       // row of the weight tile (0..127 gate / plain, 128..255 up / plain)
-        if (MODE == 2) row = (j < NJ / 2) ? (wn * (NJ / 2) + j) * 32 : 128 + (wn * (NJ / 2) + (j - NJ / 2)) * 32;
-        else row = (wn * NJ + j) * 32;
-        fbase[j] = (MODE == 2 && j >= NJ / 2) ? row - 128 : row;     // output feature offset inside the tile
-        w_off[j] = 32768 + (row + lrow) * 128;
+        for (int j = 0; j < NJ; ++j) w_off[j] = 32768 + (wrow[j] + lrow) * 128;
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) k_off[ks] = ((ks * 2 + lk) ^ sw) * 16;
@@ -339,96 +421,191 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         }
     };
 
-    const int nk = K / kBK;
     if (M > 0x7fffffff / K || 2 * N > 0x7fffffff / K) return;    // 32-bit offsets (checked on the host too)
-    issue(0, 0);
+    const int n = kt1 - kt0;                           // k-tiles of this workgroup, >= 1
+    issue(kt0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
     __syncthreads();
-    if (nk > 1) issue(1, 1);
+    if (n > 1) issue(kt0 + 1, 1);
     fetch(smem_raw, 0, 0);
-    for (int kt = 0; kt < nk - 2; ++kt) {             // tiles that still have a tile kt+2 to request
-        const unsigned char* st = smem_raw + (kt & 1) * kBigStage;
+    for (int i = 0; i < n - 2; ++i) {                 // tiles that still have a tile i+2 to request
+        const unsigned char* st = smem_raw + (i & 1) * kBigStage;
         kstep(0, true, st, 1, false, 0, 0);
         kstep(1, true, st, 2, false, 0, 0);
         kstep(0, true, st, 3, false, 0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0070);           // vmcnt(0) lgkmcnt(0): tile kt+1 landed, own reads of tile kt done
+        __builtin_amdgcn_s_waitcnt(0x0070);           // vmcnt(0) lgkmcnt(0): tile i+1 landed, own reads of tile i done
         __syncthreads();
-        kstep(1, true, smem_raw + ((kt + 1) & 1) * kBigStage, 0, true, kt + 2, kt & 1);
+        kstep(1, true, smem_raw + ((i + 1) & 1) * kBigStage, 0, true, kt0 + i + 2, i & 1);
     }
-    if (nk > 1) {                                     // tile nk-2: nothing left to request
-        const unsigned char* st = smem_raw + ((nk - 2) & 1) * kBigStage;
+    if (n > 1) {                                      // tile n-2: nothing left to request
+        const unsigned char* st = smem_raw + ((n - 2) & 1) * kBigStage;
         kstep(0, true, st, 1, false, 0, 0);
         kstep(1, true, st, 2, false, 0, 0);
         kstep(0, true, st, 3, false, 0, 0);
         __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
-        kstep(1, true, smem_raw + ((nk - 1) & 1) * kBigStage, 0, false, 0, 0);
+        kstep(1, true, smem_raw + ((n - 1) & 1) * kBigStage, 0, false, 0, 0);
     }
     {
-        const unsigned char* st = smem_raw + ((nk - 1) & 1) * kBigStage;
+        const unsigned char* st = smem_raw + ((n - 1) & 1) * kBigStage;
         kstep(0, true, st, 1, false, 0, 0);
         kstep(1, true, st, 2, false, 0, 0);
         kstep(0, true, st, 3, false, 0, 0);
         kstep(1, false, st, 0, false, 0, 0);
     }
 
-    // ---- epilogue: lane holds token (lane%32) and features 8*g + 4*(lane/32) + 0..3 of each block
+    if (PARTIAL) {
+        // partial tile in accumulator order: every (wave, j, i, r) is one 256-byte row of `ws`
+        float* base = ws + (size_t)slot * 65536 + (size_t)wave_u * NJ * 4 * 16 * 64;     // wave-uniform
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + lrow;
-        if (m >= M) continue;
-        bf16* crow = C + (size_t)m * N;
-        if (MODE == 2) {
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
-            for (int j = 0; j < NJ / 2; ++j)
+            for (int i = 0; i < 4; ++i) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + fbase[j] + 8 * g + 4 * lk;
-                    if (n < N) {
-                        bf16x4 o;
+                for (int r = 0; r < 16; ++r) base[((j * 4 + i) * 16 + r) * 64 + lane] = acc[j][i][r];
+                __builtin_amdgcn_sched_barrier(0);     // one block at a time: few registers besides the accumulators are free
+            }
+        return;
+    }
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float gt = acc[j][i][4 * g + e], up = acc[j + NJ / 2][i][4 * g + e];
-                            o[e] = (bf16)(gt / (1.0f + __expf(-gt)) * up);
-                        }
-                        *reinterpret_cast<bf16x4*>(crow + n) = o;
-                    }
-                }
-        } else {
+    for (int i = 0; i < 4; ++i)
+        big_store_block<MODE, NJ>([&](int j, int x) { return acc[j][i][x]; }, m0 + wm * 128 + i * 32 + lrow, n0, fbase,
+                                  lk, R, C, M, N);
+}
+
+// Adds the partial tiles of one split tile in range order and applies the epilogue.  One wave per
+// (wave of the main kernel, feature block j, token block i, register group g): a lane sums the 4
+// values behind one 8-byte output store.  Loads of eight ranges go out together (a range index past
+// the end re-reads the last range; its value is not added).  Grid (split tiles, units / 4).
+template <int MODE, int WN>
+__global__ __launch_bounds__(256) void gemm_big_fixup(const float* __restrict__ ws, const bf16* R, bf16* C, int M,
+                                                      int N, int tiles_m, int tiles_n, int n_dp, int splits) {
+    constexpr int NJ = 8 / WN;
+    constexpr int NJE = (MODE == 2) ? NJ / 2 : NJ;      // output blocks per wave of the main kernel
+    constexpr int NV = (MODE == 2) ? 2 : 1;             // accumulator blocks behind one output block
+    const int tile = blockIdx.x;
+    const BigTile bt = big_tile_of<MODE>(n_dp + tile, tiles_m, tiles_n);
+    const int lane = threadIdx.x & 63;
+    const int u = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int g = u & 3, i = (u >> 2) & 3, j = (u >> 4) % NJE, wave = (u >> 4) / NJE;
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = lane & 31, lk = lane >> 5;
+    int fbase[NJ], wrow[NJ];
+    big_feature_bases<MODE, NJ, WN>(wn, fbase, wrow);
+    int fb = 0;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
+    for (int jj = 0; jj < NJE; ++jj) fb = (jj == j) ? fbase[jj] : fb;
+    const int m = bt.m0 + wm * 128 + i * 32 + lrow;
+    const int n = bt.n0 + fb + 8 * g + 4 * lk;
+    float acc[NV][4];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + fbase[j] + 8 * g + 4 * lk;
-                    if (n < N) {
-                        bf16x4 o;
-                        if (MODE == 1) {
-                            const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
+    for (int v = 0; v < NV; ++v)
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[j][i][4 * g + e] + (float)rv[e]);
-                        } else {
+        for (int e = 0; e < 4; ++e) acc[v][e] = 0.f;
+    const float* base = ws + (size_t)tile * splits * 65536 + (size_t)wave * NJ * 4 * 16 * 64 + lane;
+    for (int s0 = 0; s0 < splits; s0 += 8) {
+        float t[8][NV][4];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[j][i][4 * g + e];
-                        }
-                        *reinterpret_cast<bf16x4*>(crow + n) = o;
-                    }
-                }
+        for (int q = 0; q < 8; ++q) {
+            const int sidx = (s0 + q < splits) ? s0 + q : splits - 1;
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    t[q][v][e] = base[(size_t)sidx * 65536 + (((j + v * (NJ / 2)) * 4 + i) * 16 + 4 * g + e) * 64];
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (s0 + q < splits)
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[v][e] += t[q][v][e];
+    }
+    if (m >= M || n >= N) return;
+    bf16x4 o;
+    if (MODE == 2) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float gt = acc[0][e], up = acc[NV - 1][e];
+            o[e] = (bf16)(gt / (1.0f + __expf(-gt)) * up);
+        }
+    } else if (MODE == 1) {
+        const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[0][e] + (float)rv[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[0][e];
+    }
+    *reinterpret_cast<bf16x4*>(C + (size_t)m * N + n) = o;
+}
+
+struct BigPlan {
+    int tiles_m, tiles_n, n_dp, tail, splits;
+    size_t ws_bytes;
+};
+
+static BigPlan big_plan(int mode, int M, int N, int K) {
+    BigPlan p;
+    const int out_bn = (mode == 2) ? 128 : 256;
+    p.tiles_m = (M + 255) / 256;
+    p.tiles_n = (N + out_bn - 1) / out_bn;
+    const int tiles = p.tiles_m * p.tiles_n, nk = K / kBK;
+    constexpr int kCUs = 256, kMaxTail = 128, kMaxSplits = 16, kMinKt = 4;
+    p.n_dp = tiles;
+    p.tail = 0;
+    p.splits = 1;
+    p.ws_bytes = 0;
+    const int full = tiles / kCUs * kCUs, rest = tiles - full;
+    if (full > 0 && rest > 0 && rest <= kMaxTail) {
+        int sp = kCUs / rest;
+        if (sp > kMaxSplits) sp = kMaxSplits;
+        if (sp > nk / kMinKt) sp = nk / kMinKt;
+        if (sp >= 2) {
+            const int per = (nk + sp - 1) / sp;
+            sp = (nk + per - 1) / per;               // every range non-empty
+            p.n_dp = full;
+            p.tail = rest;
+            p.splits = sp;
+            p.ws_bytes = (size_t)rest * sp * 65536 * sizeof(float);
         }
     }
+    return p;
+}
+
+static bool big_ok(int M, int N, int K) {
+    return M > 256 && K % kBK == 0 && N % 4 == 0 && (uint64_t)M * K < 0x7fffffffull &&
+           (uint64_t)2 * N * K < 0x7fffffffull;          // the large-tile kernel uses 32-bit byte offsets / 2
 }
 
 template <int MODE>
-static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, hipStream_t st) {
-    constexpr int OUT_BN = (MODE == 2) ? 128 : 256;
+static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
+                       size_t ws_bytes, hipStream_t st) {
     constexpr int LDS = 2 * kBigStage;
-    auto kern = gemm_big_kernel<MODE, BZ_BIG_WN>;
+    auto kern = gemm_big_kernel<MODE, BZ_BIG_WN, false>;
+    auto kern_part = gemm_big_kernel<MODE, BZ_BIG_WN, true>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern_part), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         attr_set = true;
     }
-    const int tiles_m = (M + 255) / 256, tiles_n = (N + OUT_BN - 1) / OUT_BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K, tiles_m, tiles_n);
+    BigPlan p = big_plan(MODE, M, N, K);
+    if (p.tail > 0 && (ws == nullptr || ws_bytes < p.ws_bytes)) {     // no scratch: every tile whole
+        p.n_dp = p.tiles_m * p.tiles_n;
+        p.tail = 0;
+        p.splits = 1;
+    }
+    hipLaunchKernelGGL(kern, dim3(p.n_dp), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K, p.tiles_m, p.tiles_n,
+                       p.n_dp, p.splits, ws);
+    if (p.tail > 0) {
+        hipLaunchKernelGGL(kern_part, dim3(p.tail * p.splits), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K,
+                           p.tiles_m, p.tiles_n, p.n_dp, p.splits, ws);
+        constexpr int kUnits = 2 * BZ_BIG_WN * ((MODE == 2) ? 4 / BZ_BIG_WN : 8 / BZ_BIG_WN) * 16;   // waves * blocks * (i, g)
+        hipLaunchKernelGGL((gemm_big_fixup<MODE, BZ_BIG_WN>), dim3(p.tail, kUnits / 4), dim3(256), 0, st, ws, r, c, M, N,
+                           p.tiles_m, p.tiles_n, p.n_dp, p.splits);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -623,8 +800,9 @@ static SkinnyPlan skinny_plan(int M, int N, int K, int mode) {
 static bool skinny_ok(int M, int N, int K) { return M >= 1 && M <= 64 && K % kBK == 0 && N % 4 == 0; }
 
 size_t gemm_workspace_bytes(int mode, int M, int N, int K) {
-    if (!skinny_ok(M, N, K)) return 0;
-    return skinny_plan(M, N, K, mode).ws_bytes;
+    if (skinny_ok(M, N, K)) return skinny_plan(M, N, K, mode).ws_bytes;
+    if (big_ok(M, N, K)) return big_plan(mode, M, N, K).ws_bytes;
+    return 0;
 }
 
 static bool skinny_applies(int mode, int M, int N, int K, const float* ws, size_t ws_bytes) {
@@ -703,9 +881,8 @@ static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, in
         launch_skinny<MODE>(a, w, r, c, M, N, K, ws, st);
     } else if (M <= 64) {
         launch_cfg<64, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
-    } else if (M > 256 && K % kBK == 0 && N % 4 == 0 && (uint64_t)M * K < 0x7fffffffull &&
-               (uint64_t)2 * N * K < 0x7fffffffull) {     // the large-tile kernel uses 32-bit byte offsets / 2
-        launch_big<MODE>(a, w, r, c, M, N, K, st);
+    } else if (big_ok(M, N, K)) {
+        launch_big<MODE>(a, w, r, c, M, N, K, ws, ws_bytes, st);
     } else {
         launch_cfg<128, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
     }

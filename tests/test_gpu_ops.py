@@ -46,6 +46,8 @@ GEMM_SHAPES = [
     (257, 4096, 512), (31, 48, 72),
     # large-tile kernel (M > 256, K a multiple of 64): ragged M, N tails, one and many K tiles
     (300, 768, 256), (700, 688, 1024), (513, 520, 64), (1030, 1024, 2048), (257, 132, 128),
+    # more than 256 tiles with a small last round (272 / 544 tiles): with a workspace the last tiles are split over K
+    (4300, 4092, 1024),
     # decode-sized problems (M <= 64, K a multiple of 64): the split-K kernel when a workspace is given
     (64, 4096, 4096), (33, 688, 1024), (7, 260, 640), (48, 1024, 14336),
 ]
@@ -111,5 +113,20 @@ def test_gemm_is_deterministic(torch):
     c2 = torch.empty_like(c1)
     op_gemm(0, a, w, None, c1, M, N, K)
     op_gemm(0, a, w, None, c2, M, N, K)
+    torch.cuda.synchronize()
+    assert torch.equal(c1.view(torch.int16), c2.view(torch.int16))
+    # split last round: partial tiles are added in a fixed order
+    from paper_2412_17246_amd import op_gemm_workspace_bytes
+    M, N, K = 4352, 4096, 512
+    nws = op_gemm_workspace_bytes(0, M, N, K)
+    assert nws > 0
+    a, _ = U.f64_to_device(rng.standard_normal((M, K)), False)
+    w, _ = U.f64_to_device(rng.standard_normal((N, K)) * 0.05, False)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    c1 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    c2 = torch.empty_like(c1)
+    op_gemm(0, a, w, None, c1, M, N, K, workspace=ws)
+    ws.fill_(0xFF)                               # stale scratch contents must not matter
+    op_gemm(0, a, w, None, c2, M, N, K, workspace=ws)
     torch.cuda.synchronize()
     assert torch.equal(c1.view(torch.int16), c2.view(torch.int16))
