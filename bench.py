@@ -44,7 +44,10 @@ PEAK_HBM_GBPS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE of this script, scaled by what the same counters read for
 # a 1 GiB device copy (x2.0 and x1.0); see profiles/gemm_big_kernel_7b_prefill_stream.txt.  L2-miss traffic
 # summed over the 8 XCD L2s, mostly served by the Infinity Cache.
-MEASURED_TRAFFIC = {("7b", 32, 6768, "gemm_gateup"): 2.105e9 + 0.150e9}
+# The gate/up figure covers the three launches of that projection (whole tiles, split last-round tiles,
+# their fix-up); the decode-attention figure covers the split-KV kernel and the combine.
+MEASURED_TRAFFIC = {("7b", 32, 6768, "gemm_gateup"): 1.898e9 + 0.149e9 + 0.069e9 + 0.061e9 + 0.061e9,
+                    ("8b_gqa", 32, 64, "attn_decode"): 0.5665e9 + 0.0119e9}
 
 
 # ------------------------------------------------------------------------------- helpers
@@ -373,7 +376,8 @@ def run_decode(args, torch, Instance):
         "kv_GB_per_step": d["bytes"] / args.steps / 1e9,
         "kernel_ms_per_step": {k: v["ms"] / args.steps for k, v in prof.items() if v["launches"]},
         "roofline": {"bound": "hbm", "kernel": "attn_decode", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBPS, "traffic": None, "launches": d["launches"],
+                     "frac": achieved / PEAK_HBM_GBPS,
+                     "traffic": MEASURED_TRAFFIC.get((shape.name, shape.L, B, "attn_decode")), "launches": d["launches"],
                      "avg_ms": d["ms"] / d["launches"]},
     })
     if split_note:
