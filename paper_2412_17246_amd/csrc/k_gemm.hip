@@ -198,16 +198,25 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const bf16*
 
 // ---------------------------------------------------------------------------------------------
 // Large-tile kernel for prefill-sized problems (K a multiple of 64, N a multiple of 4):
-// 256x256x64 workgroup tile, 4 waves, 128x128 per wave (256 accumulator registers), two 64 KiB LDS
-// stages filled by direct global->LDS loads (16 bytes per lane, no register staging).  A wave's
-// load instruction writes 1 KiB of LDS in lane order, i.e. 8 rows of 128 bytes; bank conflicts are
+// 256x256x64 workgroup tile, 4 waves, 128x128 per wave (256 accumulator registers).  Operands reach
+// LDS by direct global->LDS loads (16 bytes per lane, no register staging).  A wave's load
+// instruction writes 1 KiB of LDS in lane order, i.e. 8 rows of 128 bytes; bank conflicts are
 // avoided by permuting WHICH 16-byte piece of its row each lane fetches (an XOR swizzle applied on
 // the global side) and reading operands with the same permutation.  The weight tile feeds the
 // MFMA's row operand and the activation tile its column operand, so a lane ends up with 4
 // consecutive output features of one token: 8-byte stores, and gate/up of the same feature in
 // the same lane for the SwiGLU epilogue.
+//
+// LDS is a ring of five 32 KiB slots, each holding one operand's 256 rows of one k-tile: the tile
+// being multiplied, the next one, and the activation half of the one after.  What decides the
+// schedule is the cost of ISSUING a load: a 1 KiB load holds its wave's instruction stream for
+// about 64 cycles when the four waves issue together (the address unit is shared), and a wave that
+// cannot issue cannot feed the matrix pipe either.  So loads go out one every four MFMAs, spread
+// over the whole tile, into the two slots the previous tile released, and the wait before a
+// tile's barrier leaves the newest 32 KiB in flight.
 // ---------------------------------------------------------------------------------------------
-constexpr int kBigStage = (256 + 256) * kBK * (int)sizeof(bf16);    // 65536
+constexpr int kBigSlot = 256 * kBK * (int)sizeof(bf16);      // 32768: one operand's 256 rows of one k-tile
+constexpr int kBigSlots = 5;
 
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
@@ -354,20 +363,24 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         }
         b_off[j] = ((uint32_t)br * (uint32_t)K + c * 8) * 2u;
     }
-    auto issue_piece = [&](int kt, int stage, int q) {     // q in [0, 2*NCH): A chunks at even q, W chunks at odd q
-        const int j = q >> 1;
-        unsigned char* sa = smem_raw + stage * kBigStage + wave_u * NCH * 1024;
-        if ((q & 1) == 0) {
-            const char* ak = reinterpret_cast<const char*>(A + (size_t)kt * kBK);
-            __builtin_amdgcn_global_load_lds((gptr_t)(ak + a_off[j]), (lptr_t)(sa + j * 1024), 16, 0, 0);
+    // Unit u = 2t is the activation half of k-tile t, u = 2t + 1 its weight half; unit u lives in slot
+    // u % 5.  Piece q in [0, NCH) of a unit is this wave's q-th 1 KiB chunk.  Past the last k-tile the
+    // last one is fetched again (into a slot nobody reads any more) so that every tile issues the
+    // same number of loads and the wait counts below hold for every tile.
+    auto issue_piece = [&](int kt, int slot, bool weights, int q) {
+        unsigned char* sa = smem_raw + slot * kBigSlot + (wave_u * NCH + q) * 1024;
+        const int t = kt < kt1 ? kt : kt1 - 1;
+        if (!weights) {
+            const char* ak = reinterpret_cast<const char*>(A + (size_t)t * kBK);
+            __builtin_amdgcn_global_load_lds((gptr_t)(ak + a_off[q]), (lptr_t)sa, 16, 0, 0);
         } else {
-            const char* wk = reinterpret_cast<const char*>(W + (size_t)kt * kBK);
-            __builtin_amdgcn_global_load_lds((gptr_t)(wk + b_off[j]), (lptr_t)(sa + 32768 + j * 1024), 16, 0, 0);
+            const char* wk = reinterpret_cast<const char*>(W + (size_t)t * kBK);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wk + b_off[q]), (lptr_t)sa, 16, 0, 0);
         }
     };
-    auto issue = [&](int kt, int stage) {
+    auto issue_unit = [&](int kt, int slot, bool weights) {
 #pragma unroll
-        for (int q = 0; q < 2 * NCH; ++q) issue_piece(kt, stage, q);
+        for (int q = 0; q < NCH; ++q) issue_piece(kt, slot, weights, q);
     };
 
     f32x16 acc[NJ][4];      // [feature block][token block]
@@ -387,72 +400,80 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         int wrow[NJ];
         big_feature_bases<MODE, NJ, WN>(wn, fbase, wrow);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) w_off[j] = 32768 + (wrow[j] + lrow) * 128;
+        for (int j = 0; j < NJ; ++j) w_off[j] = (wrow[j] + lrow) * 128;
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) k_off[ks] = ((ks * 2 + lk) ^ sw) * 16;
 
     // ---- main loop.  Every k-step is NMMA MFMAs in a fixed order; between them, one by one, go the
-    // LDS reads that fetch the operands of the NEXT k-step and (in the last k-step of a tile) the
-    // global->LDS loads of the tile after next.  The order is pinned with scheduling barriers so
-    // the matrix pipe never waits behind a burst of memory instructions.  The tile barrier sits
-    // before the last k-step, whose operands are already in registers.
+    // LDS reads that fetch the operands of the NEXT k-step and, after every fourth MFMA, one
+    // global->LDS load.  The order is pinned with scheduling barriers so the matrix pipe never waits
+    // behind a burst of memory instructions.  The tile barrier sits before the last k-step, whose
+    // operands are already in registers; it is a bare s_barrier (the waits are written out here; a
+    // full __syncthreads would drain the loads that are meant to stay in flight).
+    //
+    // The two slots tile i - 1 released at its barrier are refilled as follows: last k-step of tile
+    // i - 1 and first of tile i: weights of tile i + 1 (needed first); k-steps 1 and 2 of tile i:
+    // activations of tile i + 2.  Before the barrier of tile i everything but those activations must
+    // have landed.
     bf16x8 xf[2][4], wf[2][NJ];
-    auto fetch_piece = [&](const unsigned char* st, int ks, int buf, int q) {   // order of first use
-        if (q == 0) wf[buf][0] = *reinterpret_cast<const bf16x8*>(st + w_off[0] + k_off[ks]);
-        else if (q <= 4) xf[buf][q - 1] = *reinterpret_cast<const bf16x8*>(st + x_off[q - 1] + k_off[ks]);
-        else wf[buf][q - 4] = *reinterpret_cast<const bf16x8*>(st + w_off[q - 4] + k_off[ks]);
+    auto fetch_piece = [&](const unsigned char* sx, const unsigned char* sw_, int ks, int buf, int q) {   // order of first use
+        if (q == 0) wf[buf][0] = *reinterpret_cast<const bf16x8*>(sw_ + w_off[0] + k_off[ks]);
+        else if (q <= 4) xf[buf][q - 1] = *reinterpret_cast<const bf16x8*>(sx + x_off[q - 1] + k_off[ks]);
+        else wf[buf][q - 4] = *reinterpret_cast<const bf16x8*>(sw_ + w_off[q - 4] + k_off[ks]);
     };
-    auto fetch = [&](const unsigned char* st, int ks, int buf) {
-#pragma unroll
-        for (int q = 0; q < NFETCH; ++q) fetch_piece(st, ks, buf, q);
-    };
-    // one k-step: MFMAs from buffer `cur`; optionally fetch k-step `nks` of stage `fst` into the
-    // other buffer and request tile `ikt` into stage `istage`
-    auto kstep = [&](int cur, bool do_fetch, const unsigned char* fst, int nks, bool do_issue, int ikt, int istage) {
+    constexpr int PER = NCH / 2;                       // loads per wave per k-step
+    constexpr int GAP = NMMA / PER;                    // MFMAs between two loads of a wave
+    // one k-step: MFMAs from buffer `cur`; fetch k-step `nks` of the tile in slots (sx, sw_) into the
+    // other buffer; request pieces p0 .. p0 + PER - 1 of one operand of k-tile `ikt` into slot `islot`
+    auto kstep = [&](int cur, const unsigned char* sx, const unsigned char* sw_, int nks, int ikt, int islot, bool iweights,
+                     int p0) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < NMMA; ++q) {
             const int j = q >> 2, i = q & 3;
             acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[j][i], 0, 0, 0);
-            if (do_fetch && q < NFETCH) fetch_piece(fst, nks, cur ^ 1, q);
-            if (do_issue && q < 2 * NCH) issue_piece(ikt, istage, q);
+            if (q < NFETCH) fetch_piece(sx, sw_, nks, cur ^ 1, q);
+            if (q % GAP == GAP - 1) issue_piece(ikt, islot, iweights, p0 + q / GAP);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     if (M > 0x7fffffff / K || 2 * N > 0x7fffffff / K) return;    // 32-bit offsets (checked on the host too)
     const int n = kt1 - kt0;                           // k-tiles of this workgroup, >= 1
-    issue(kt0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
-    __syncthreads();
-    if (n > 1) issue(kt0 + 1, 1);
-    fetch(smem_raw, 0, 0);
-    for (int i = 0; i < n - 2; ++i) {                 // tiles that still have a tile i+2 to request
-        const unsigned char* st = smem_raw + (i & 1) * kBigStage;
-        kstep(0, true, st, 1, false, 0, 0);
-        kstep(1, true, st, 2, false, 0, 0);
-        kstep(0, true, st, 3, false, 0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0070);           // vmcnt(0) lgkmcnt(0): tile i+1 landed, own reads of tile i done
-        __syncthreads();
-        kstep(1, true, smem_raw + ((i + 1) & 1) * kBigStage, 0, true, kt0 + i + 2, i & 1);
+    issue_unit(kt0, 0, false);
+    issue_unit(kt0, 1, true);
+    issue_unit(kt0 + 1, 2, false);
+#pragma unroll
+    for (int q = 0; q < NCH / 2; ++q) issue_piece(kt0 + 1, 3, true, q);
+    if (NCH == 8) __builtin_amdgcn_s_waitcnt(0x0F7C);  // vmcnt(12): tile kt0 landed
+    else __builtin_amdgcn_s_waitcnt(0x0F76);           // vmcnt(6)
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < NFETCH; ++q) fetch_piece(smem_raw, smem_raw + kBigSlot, 0, 0, q);
+    int sa = 0;                                        // slot of the current tile's activations; its weights follow
+    for (int i = 0; i < n; ++i) {
+        const int sw1 = (sa + 1 >= kBigSlots) ? sa + 1 - kBigSlots : sa + 1;
+        const int na = (sa + 2 >= kBigSlots) ? sa + 2 - kBigSlots : sa + 2;      // next tile's slots
+        const int nw = (sa + 3 >= kBigSlots) ? sa + 3 - kBigSlots : sa + 3;
+        const int fa2 = (sa + 4 >= kBigSlots) ? sa + 4 - kBigSlots : sa + 4;     // where tile i + 2's activations go
+        const unsigned char* sx = smem_raw + sa * kBigSlot;
+        const unsigned char* sww = smem_raw + sw1 * kBigSlot;
+        kstep(0, sx, sww, 1, kt0 + i + 1, nw, true, NCH / 2);
+        kstep(1, sx, sww, 2, kt0 + i + 2, fa2, false, 0);
+        kstep(0, sx, sww, 3, kt0 + i + 2, fa2, false, NCH / 2);
+        // tile i + 1 has landed (only the NCH newest loads, activations of tile i + 2, may be in flight);
+        // own LDS reads of tile i are done
+        if (NCH == 8) __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
+        else __builtin_amdgcn_s_waitcnt(0x0074);            // vmcnt(4) lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        // tile i + 2's weights, first half, into the slot this tile's activations just left
+        kstep(1, smem_raw + na * kBigSlot, smem_raw + nw * kBigSlot, 0, kt0 + i + 2, sa, true, 0);
+        sa = na;
     }
-    if (n > 1) {                                      // tile n-2: nothing left to request
-        const unsigned char* st = smem_raw + ((n - 2) & 1) * kBigStage;
-        kstep(0, true, st, 1, false, 0, 0);
-        kstep(1, true, st, 2, false, 0, 0);
-        kstep(0, true, st, 3, false, 0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0070);
-        __syncthreads();
-        kstep(1, true, smem_raw + ((n - 1) & 1) * kBigStage, 0, false, 0, 0);
-    }
-    {
-        const unsigned char* st = smem_raw + ((n - 1) & 1) * kBigStage;
-        kstep(0, true, st, 1, false, 0, 0);
-        kstep(1, true, st, 2, false, 0, 0);
-        kstep(0, true, st, 3, false, 0, 0);
-        kstep(1, false, st, 0, false, 0, 0);
-    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // no LDS write may be in flight when the workgroup ends
 
     if (PARTIAL) {
         // partial tile in accumulator order: every (wave, j, i, r) is one 256-byte row of `ws`
@@ -582,7 +603,7 @@ static bool big_ok(int M, int N, int K) {
 template <int MODE>
 static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
                        size_t ws_bytes, hipStream_t st) {
-    constexpr int LDS = 2 * kBigStage;
+    constexpr int LDS = kBigSlots * kBigSlot;
     auto kern = gemm_big_kernel<MODE, BZ_BIG_WN, false>;
     auto kern_part = gemm_big_kernel<MODE, BZ_BIG_WN, true>;
     static bool attr_set = false;
