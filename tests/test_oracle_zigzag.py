@@ -95,13 +95,17 @@ def test_program_objective_and_constraints_on_hand_cases():
     assert Z.program_constraints_hold(3, [1, 1], 1.0)[2] is True       # 1 <= 1 + 0
     assert Z.program_constraints_hold(3, [1, 1], 1.5)[2] is False      # 1.5 <= 1 fails
     # brute force on a case small enough to enumerate by hand: L = 2, N = 2, time_l = 0.5.
-    # feasible T (C2: T1+T2 <= 2-T1; C3: 0.5*T2 <= T1 + (T2-1)): (0,2) obj 2+2=4/2=2 ... best is T=(0,2)? enumerate:
-    best = Z.solve_program_bruteforce(2, 2, 0.5)
-    feas = []
+    # C2 (request 2): 2*T1 + T2 <= 2;  C3 (request 2): 0.5*T2 <= T1 + (T2 - 1).
+    #   (0,0): C3 0 <= -1 fails      (0,1): C3 0.5 <= 0 fails     (0,2): both hold, S = (2,0), latencies 2, 2 -> 2.0
+    #   (1,0): both hold, S = (1,2), latencies 1, 3 -> 2.0        every other T breaks C2
+    feasible = {(0, 2), (1, 0)}
     for t1 in range(3):
         for t2 in range(3):
-            c = Z.program_constraints_hold(2, [t1, t2], 0.5)
-            if all(c):
-                feas.append((Z.program_objective(2, [t1, t2]), [t1, t2]))
-    assert best is not None and best[0] == min(f[0] for f in feas)
-    assert (2 - best[1][0]) + (2 - best[1][0]) + (2 - best[1][1]) == 2 * best[0]
+            assert all(Z.program_constraints_hold(2, [t1, t2], 0.5)) == ((t1, t2) in feasible), (t1, t2)
+    assert Z.program_objective(2, [0, 2]) == 2.0 and Z.program_objective(2, [1, 0]) == 2.0
+    best = Z.solve_program_bruteforce(2, 2, 0.5)
+    assert best is not None and best[0] == 2.0 and tuple(best[1]) in feasible
+    # with time_l = 0, C3 becomes 0 <= T1 + T2 - 1 and (0,1) joins the feasible set
+    best0 = Z.solve_program_bruteforce(2, 2, 0.0)
+    # feasible now: (0,1) [S=(2,1): 2, 3 -> 2.5], (0,2) [2.0], (1,0) [2.0]; minimum still 2.0
+    assert best0[0] == 2.0
