@@ -600,18 +600,29 @@ static bool big_ok(int M, int N, int K) {
            (uint64_t)2 * N * K < 0x7fffffffull;          // the large-tile kernel uses 32-bit byte offsets / 2
 }
 
+// The large-tile kernel needs the CU's whole 160 KiB of LDS; if the runtime does not grant it (it is a
+// property of the device, asked once per instantiation) the caller takes the 128x128 kernel instead.
+template <int MODE>
+static bool big_available() {
+    constexpr int LDS = kBigSlots * kBigSlot;
+    static int state = 0;                               // 0 not asked yet, 1 granted, -1 refused
+    if (state == 0) {
+        const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, false>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, true>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        state = (e1 == hipSuccess && e2 == hipSuccess) ? 1 : -1;
+        if (state < 0) (void)hipGetLastError();         // the refusal is handled here, not reported by a later call
+    }
+    return state > 0;
+}
+
 template <int MODE>
 static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
                        size_t ws_bytes, hipStream_t st) {
     constexpr int LDS = kBigSlots * kBigSlot;
     auto kern = gemm_big_kernel<MODE, BZ_BIG_WN, false>;
     auto kern_part = gemm_big_kernel<MODE, BZ_BIG_WN, true>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern_part), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        attr_set = true;
-    }
     BigPlan p = big_plan(MODE, M, N, K);
     if (p.tail > 0 && (ws == nullptr || ws_bytes < p.ws_bytes)) {     // no scratch: every tile whole
         p.n_dp = p.tiles_m * p.tiles_n;
@@ -633,13 +644,16 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 // Skinny kernel for decode-sized problems (M <= 64 rows): the weights are read from HBM exactly
 // once and that read is the whole cost, so the job is to keep every CU streaming.  Work is cut
 // into 64-feature tiles times KSPLIT slices of K (a function of the shape only); each workgroup
-// streams its weight slice and the matching activation slice through a 4-deep ring of 16 KiB LDS
+// streams its weight slice and the matching activation slice through a ring of 16 KiB LDS
 // stages filled by direct global->LDS loads, multiplies with one 32x32x16 MFMA per wave and
 // k-step, and writes an fp32 partial tile.  A second kernel adds the slices in slice order and
 // applies the epilogue, so the result is deterministic.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSkStage = (64 + 64) * kBK * (int)sizeof(bf16);    // 16384
-constexpr int kSkStages = 4;
+#ifndef BZ_SK_STAGES
+#define BZ_SK_STAGES 4
+#endif
+constexpr int kSkStages = BZ_SK_STAGES;    // 16 KiB each; two workgroups share a CU's 160 KiB
 
 // GU (gate/up projection): a tile is 32 gate features (weight rows n0..n0+31) and the 32 matching up
 // features (rows N + n0..), so that with a single k-slice the workgroup holds both factors of
@@ -701,19 +715,24 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restr
     const int x_off = (wt * 32 + lrow) * 128;
     const int w_off = 8192 + (wf * 32 + lrow) * 128;
 
-    // prologue: up to three tiles in flight
-    if (n > 0) issue(kt0, 0);
-    if (n > 1) issue(kt0 + 1, 1);
-    if (n > 2) issue(kt0 + 2, 2);
+    // prologue: up to kSkStages - 1 tiles in flight
+#pragma unroll
+    for (int t = 0; t < kSkStages - 1; ++t)
+        if (n > t) issue(kt0 + t, t);
+    int cur = 0, nxt = kSkStages - 1;                // stage of tile i; stage the tile requested next goes to
     for (int i = 0; i < n; ++i) {
-        // tile i must have landed; the two tiles requested after it may still be in flight
-        if (i + 2 < n) __builtin_amdgcn_s_waitcnt(0x0078);       // vmcnt(8) lgkmcnt(0)
-        else if (i + 1 < n) __builtin_amdgcn_s_waitcnt(0x0074);  // vmcnt(4) lgkmcnt(0)
-        else __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) lgkmcnt(0)
-        __builtin_amdgcn_s_barrier();                            // everyone's part landed; stage (i-1)%4 is free
+        // tile i must have landed; the tiles requested after it (4 loads each) may still be in flight
+        const int later = (n - 1 - i < kSkStages - 2) ? n - 1 - i : kSkStages - 2;
+        if (later >= 3) __builtin_amdgcn_s_waitcnt(0x007C);        // vmcnt(12) lgkmcnt(0)
+        else if (later == 2) __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
+        else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0074);   // vmcnt(4) lgkmcnt(0)
+        else __builtin_amdgcn_s_waitcnt(0x0070);                   // vmcnt(0) lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();                              // everyone's part landed; the stage of tile i-1 is free
         __builtin_amdgcn_sched_barrier(0);
-        if (i + 3 < n) issue(kt0 + i + 3, (i + 3) & 3);
-        const unsigned char* st = smem_raw + (i & 3) * kSkStage;
+        if (i + kSkStages - 1 < n) issue(kt0 + i + kSkStages - 1, nxt);
+        const unsigned char* st = smem_raw + cur * kSkStage;
+        nxt = cur;
+        cur = (cur + 1 == kSkStages) ? 0 : cur + 1;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int ko = ((ks * 2 + lk) ^ sw) * 16;
@@ -902,7 +921,7 @@ static void launch_mode(const bf16* a, const bf16* w, const bf16* r, bf16* c, in
         launch_skinny<MODE>(a, w, r, c, M, N, K, ws, st);
     } else if (M <= 64) {
         launch_cfg<64, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
-    } else if (big_ok(M, N, K)) {
+    } else if (big_ok(M, N, K) && big_available<MODE>()) {
         launch_big<MODE>(a, w, r, c, M, N, K, ws, ws_bytes, st);
     } else {
         launch_cfg<128, 128, 2, 2, MODE>(a, w, r, c, M, N, K, st);
