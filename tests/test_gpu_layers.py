@@ -245,6 +245,22 @@ def test_mixed_ragged_batch(torch, fp32, shape):
             assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
 
 
+@pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
+@pytest.mark.parametrize("shape", [MIX, G8], ids=lambda s: s.name)
+def test_small_mixed_batch_takes_the_decode_sized_kernels(torch, fp32, shape):
+    # at most 64 rows in all, so the projections leave split-K partial sums that the rotary/append and norm
+    # kernels fold; the batch still holds prefills long enough to write whole 16-position groups of V
+    # (from partial sums), a chunked prefill that starts inside a group, and decode tokens
+    seqs = [(20, 0), (1, 40), (17, 16), (1, 0), (19, 7), (1, 300)]
+    assert sum(n for n, _ in seqs) <= 64
+    got, want, q_start = _mixed_case(torch, shape, fp32, seqs)
+    tol = _tol(fp32)
+    assert U.rel_err(got, want) <= tol
+    for i in range(len(seqs)):
+        a, b = q_start[i], q_start[i + 1]
+        assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
+
+
 def test_first_causal_token_returns_v_row_on_the_gpu(torch):
     """Wo = identity-like routing is not available with random weights, so check the attention
     output itself: with one visible key, softmax weight is exactly 1 and the output is the V row,
