@@ -147,7 +147,7 @@ void launch_reduce_residual_rmsnorm(act_t* x, const float* partial, int ksplit, 
 template <bool REDUCE>
 __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qkv, const float* __restrict__ partial,
                                                           int ksplit, const float* __restrict__ tab, BatchView bv,
-                                                          KvView kv, int Hq, int n_vblocks) {
+                                                          KvView kv, int Hq, int n_vblocks, int tsplit) {
     const int d = kv.d, Hkv = kv.Hkv, half = d >> 1;
     const int nqkv = (Hq + 2 * Hkv) * d;
     if ((int)blockIdx.x < n_vblocks) {
@@ -185,7 +185,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
         }
         return;
     }
-    const int t = blockIdx.x - n_vblocks;
+    // a token's work is shared by `tsplit` workgroups (small batches: more CUs than tokens)
+    const int t = (blockIdx.x - n_vblocks) / tsplit, part = (blockIdx.x - n_vblocks) % tsplit;
     const int s = bv.token_seq[t];
     const int before = bv.kv_before[s];
     const int pos = before + (t - bv.q_start[s]);
@@ -217,10 +218,14 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
     // V of a token that is stored element by element: first vector requested before the rotation so
     // that both round trips to memory overlap
     constexpr int kPass = 2048;
-    const int vcol = (Hq + Hkv) * d, nv = Hkv * d;
+    const int nv_all = Hkv * d;
+    const int v_per = ((nv_all + tsplit - 1) / tsplit + 7) & ~7;          // this workgroup's share of the V row
+    const int v_lo = part * v_per;
+    const int nv = v_lo >= nv_all ? 0 : (nv_all - v_lo < v_per ? nv_all - v_lo : v_per);
+    const int vcol = (Hq + Hkv) * d + v_lo;
     float vpre[8];
     if (!v_by_group && (int)threadIdx.x * 8 < nv) fetch8(vcol + threadIdx.x * 8, vpre);
-    for (int u = threadIdx.x; u < rot_units; u += blockDim.x) {
+    for (int u = part * blockDim.x + threadIdx.x; u < rot_units; u += tsplit * blockDim.x) {
         {
             const int head = u / units_per_head;          // 0..Hq-1 query heads, then key heads
             const int j0 = (u - head * units_per_head) * 8;
@@ -259,7 +264,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
             }
             __syncthreads();
             for (int u = threadIdx.x; u < cnt; u += blockDim.x) {
-                const int kvh = (base + u) / d, j = (base + u) - kvh * d;
+                const int kvh = (v_lo + base + u) / d, j = (v_lo + base + u) - kvh * d;
                 kv.v[slot_base + (size_t)kvh * cap * d + v_elem_offset(pos, j, d)] = vst[u];
             }
             __syncthreads();
@@ -271,16 +276,18 @@ void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, 
                         hipStream_t st) {
     if (bv.T <= 0) return;
     const int nvb = bv.n_prefill_items * 16;
-    hipLaunchKernelGGL(rope_append_kernel<false>, dim3(nvb + bv.T), dim3(256), 0, st, qkv, nullptr, 0, rope_tab, bv, kv,
-                       Hq, nvb);
+    const int tsplit = bv.T < 256 ? 4 : 1;
+    hipLaunchKernelGGL(rope_append_kernel<false>, dim3(nvb + bv.T * tsplit), dim3(256), 0, st, qkv, nullptr, 0, rope_tab,
+                       bv, kv, Hq, nvb, tsplit);
 }
 
 void launch_rope_append_reduce(act_t* qkv, const float* partial, int ksplit, const float* rope_tab,
                                const BatchView& bv, const KvView& kv, int Hq, hipStream_t st) {
     if (bv.T <= 0) return;
     const int nvb = bv.n_prefill_items * 16;
-    hipLaunchKernelGGL(rope_append_kernel<true>, dim3(nvb + bv.T), dim3(256), 0, st, qkv, partial, ksplit, rope_tab, bv,
-                       kv, Hq, nvb);
+    const int tsplit = bv.T < 256 ? 4 : 1;
+    hipLaunchKernelGGL(rope_append_kernel<true>, dim3(nvb + bv.T * tsplit), dim3(256), 0, st, qkv, partial, ksplit,
+                       rope_tab, bv, kv, Hq, nvb, tsplit);
 }
 
 // ---------------------------------------------------------------------------------------------
