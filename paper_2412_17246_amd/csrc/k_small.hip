@@ -115,7 +115,9 @@ __global__ __launch_bounds__(THREADS) void rmsnorm_kernel(act_t* __restrict__ x,
 void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, float eps, hipStream_t st) {
     if (T <= 0) return;
     act_t* xm = const_cast<act_t*>(x);       // not written without REDUCE
-    if (H >= 2048) {
+    if (H >= 4096 && T <= 256) {             // few rows: more threads per row shorten each thread's chain of loads
+        hipLaunchKernelGGL((rmsnorm_kernel<512, false>), dim3(T), dim3(512), 0, st, xm, nullptr, 0, T, gain, y, H, eps);
+    } else if (H >= 2048) {
         hipLaunchKernelGGL((rmsnorm_kernel<256, false>), dim3(T), dim3(256), 0, st, xm, nullptr, 0, T, gain, y, H, eps);
     } else {
         hipLaunchKernelGGL((rmsnorm_kernel<64, false>), dim3(T), dim3(64), 0, st, xm, nullptr, 0, T, gain, y, H, eps);
@@ -125,7 +127,9 @@ void launch_rmsnorm(const act_t* x, const bf16* gain, act_t* y, int T, int H, fl
 void launch_reduce_residual_rmsnorm(act_t* x, const float* partial, int ksplit, const bf16* gain, act_t* y, int T,
                                     int H, float eps, hipStream_t st) {
     if (T <= 0) return;
-    if (H >= 2048) {
+    if (H >= 4096 && T <= 256) {
+        hipLaunchKernelGGL((rmsnorm_kernel<512, true>), dim3(T), dim3(512), 0, st, x, partial, ksplit, T, gain, y, H, eps);
+    } else if (H >= 2048) {
         hipLaunchKernelGGL((rmsnorm_kernel<256, true>), dim3(T), dim3(256), 0, st, x, partial, ksplit, T, gain, y, H, eps);
     } else {
         hipLaunchKernelGGL((rmsnorm_kernel<64, true>), dim3(T), dim3(64), 0, st, x, partial, ksplit, T, gain, y, H, eps);
