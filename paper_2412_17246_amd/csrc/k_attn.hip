@@ -80,18 +80,21 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
 
     // tile -> LDS: wave w moves 1 KiB pieces w*NL .. w*NL+NL-1 of the K tile and of the V tile.  A
     // block past the last visible one is replaced by the last visible block (its scores are masked).
-    auto issue = [&](int tile, int stage) {
+    // load q in [0, 2*NL) of a tile: K pieces first (needed first), then V pieces
+    auto issue_one = [&](int tile, int stage, int q) {
         bf16* st = smem + stage * STAGE;
+        const int j = q % NL;
+        const int piece = wave_u * NL + j;                   // 512 elements each
+        const int blk = piece / (BLK / 512), off = (piece % (BLK / 512)) * 512;
+        int kb = tile * 2 + blk;
+        if (kb > last_blk) kb = last_blk;
+        const size_t src = (size_t)kb * BLK + off + lane * 8;
+        if (q < NL) __builtin_amdgcn_global_load_lds((gptr_t)(Kc + src), (lptr_t)(st + piece * 512), 16, 0, 0);
+        else __builtin_amdgcn_global_load_lds((gptr_t)(Vc + src), (lptr_t)(st + 2 * BLK + piece * 512), 16, 0, 0);
+    };
+    auto issue = [&](int tile, int stage) {
 #pragma unroll
-        for (int j = 0; j < NL; ++j) {
-            const int piece = wave_u * NL + j;               // 512 elements each
-            const int blk = piece / (BLK / 512), off = (piece % (BLK / 512)) * 512;
-            int kb = tile * 2 + blk;
-            if (kb > last_blk) kb = last_blk;
-            const size_t src = (size_t)kb * BLK + off + lane * 8;
-            __builtin_amdgcn_global_load_lds((gptr_t)(Kc + src), (lptr_t)(st + piece * 512), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(Vc + src), (lptr_t)(st + 2 * BLK + piece * 512), 16, 0, 0);
-        }
+        for (int q = 0; q < 2 * NL; ++q) issue_one(tile, stage, q);
     };
     issue(0, 0);
 
@@ -113,11 +116,18 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
         const int kbase = tile * BK;
         __builtin_amdgcn_s_waitcnt(0x0070);                  // own pieces of this tile landed, own LDS reads done
         __syncthreads();                                     // everyone's pieces landed; the other stage is free
-        if (tile + 1 < ntiles) issue(tile + 1, (tile + 1) & 1);
-        if (kbase <= wave_max_pos) {                         // wave-uniform: tile not fully masked for this wave
+        // after the last tile the same tile is requested once more into the idle stage: the load schedule
+        // then needs no branch between the MFMAs
+        const int nxt = tile + 1 < ntiles ? tile + 1 : tile;
+        if (kbase > wave_max_pos) {                          // wave-uniform: tile fully masked for this wave
+            issue(nxt, (tile + 1) & 1);
+        } else {
             const bf16* Ks = smem + (tile & 1) * STAGE;
             const bf16* Vs = Ks + 2 * BLK;
             f32x16 sacc[2];
+            // the next tile's loads go out one by one between the score MFMAs: a load holds the wave's
+            // instruction stream for tens of cycles, which an MFMA in flight covers
+            constexpr int EVERY = (2 * KS) / (2 * NL);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -126,6 +136,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
                 for (int ks = 0; ks < KS; ++ks) {
                     const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[kb * BLK + ((ks * 2 + lh) * 32 + lq) * 8]);
                     sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
+                    const int m = kb * KS + ks;
+                    if (m % EVERY == EVERY - 1) issue_one(nxt, (tile + 1) & 1, m / EVERY);
                 }
             }
             if (kbase + BK - 1 > wave_min_pos) {             // wave-uniform: the diagonal crosses this tile
@@ -179,6 +191,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
         }
     }
 
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // no LDS write may be in flight when the workgroup ends
     if (valid) {
         const float inv = 1.0f / l;
         bf16* op = out + (size_t)(q0 + qi) * Hq * D + h * D;
