@@ -261,6 +261,20 @@ def test_small_mixed_batch_takes_the_decode_sized_kernels(torch, fp32, shape):
         assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
 
 
+@pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
+@pytest.mark.parametrize("shape", [MIX64, G8], ids=lambda s: s.name)
+def test_long_caches(torch, fp32, shape):
+    # decode over caches of more than 16 chunks of 256 positions (the combine step then takes its partial
+    # results in several batches), at and just past a chunk boundary, and a chunked prefill whose new
+    # tokens sit on top of a long cache, and one prefill of several thousand tokens from an empty cache
+    seqs = [(1, 9000), (1, 4095), (1, 4096), (70, 5000), (1, 4351), (3001, 0)]
+    got, want, q_start = _mixed_case(torch, shape, fp32, seqs)
+    tol = _tol(fp32)
+    for i in range(len(seqs)):
+        a, b = q_start[i], q_start[i + 1]
+        assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
+
+
 def test_first_causal_token_returns_v_row_on_the_gpu(torch):
     """Wo = identity-like routing is not available with random weights, so check the attention
     output itself: with one visible key, softmax weight is exactly 1 and the output is the V row,
