@@ -488,6 +488,50 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
             }
         return;
     }
+    if (MODE == 1) {
+        // R may be C itself (the residual stream is updated in place), so written as load-then-store per
+        // element the compiler has to keep every load behind the store before it.  A lane reads exactly
+        // the addresses it writes: fetch a whole token block's residual values first, and the next
+        // block's before this block's stores go out.
+        bf16x4 rv[2][NJ * 4];
+        auto load_r = [&](int i, int buf) {
+            int m = m0 + wm * 128 + i * 32 + lrow;
+            if (m > M - 1) m = M - 1;                   // rows and features past the end: a valid address, value unused
+            const bf16* rrow = R + (size_t)m * N;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    int n = n0 + fbase[j] + 8 * g + 4 * lk;
+                    if (n > N - 4) n = N - 4;
+                    rv[buf][j * 4 + g] = *reinterpret_cast<const bf16x4*>(rrow + n);
+                }
+        };
+        load_r(0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (i + 1 < 4) load_r(i + 1, (i + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            const int m = m0 + wm * 128 + i * 32 + lrow;
+            if (m < M) {
+                bf16* crow = C + (size_t)m * N;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = n0 + fbase[j] + 8 * g + 4 * lk;
+                        if (n < N) {
+                            bf16x4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[j][i][4 * g + e] + (float)rv[i & 1][j * 4 + g][e]);
+                            *reinterpret_cast<bf16x4*>(crow + n) = o;
+                        }
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         big_store_block<MODE, NJ>([&](int j, int x) { return acc[j][i][x]; }, m0 + wm * 128 + i * 32 + lrow, n0, fbase,
