@@ -171,7 +171,11 @@ int bz_sync(bz_instance* inst);                  /* waits for both streams */
  * arrive one by one).  Enqueues chunked async copies of `n` == layer_bytes bytes from pinned host
  * memory `host` into layer i's slot of the weight arena on the copy stream, records the layer's
  * event and returns at once.  `host` is borrowed until the layer is resident.  Layers may be
- * requested in any order.  BZ_EBUSY if layer i is loading or resident. */
+ * requested in any order.  BZ_EBUSY if layer i is loading or resident.
+ * The bytes go over in blob order, which is the order the layer reads them (attention weights
+ * first, down projection last), and an event is also recorded behind each group of tensors that one
+ * stage of the layer needs; bz_run_layers uses them (see there).  The layer counts as resident, for
+ * the frontier and every query below, only when all of it has landed. */
 int bz_load_layer(bz_instance* inst, int layer, const void* host, size_t n);
 /* Same, from a device buffer (a resident peer's copy: one hop of section 5.1's forwarding chain). */
 int bz_load_layer_from_device(bz_instance* inst, int layer, const void* dev, size_t n);
@@ -238,9 +242,13 @@ int bz_batch_advance(bz_instance* inst, bz_batch* batch);
 
 /* Runs decoder layers [a,b) in order on the compute stream over `hidden` — device, [T,H]
  * activation elements, updated in place — appending the new tokens' K/V of those layers to the
- * instance's cache.  Before layer i's first kernel the compute stream waits on layer i's ingest
- * event, so the call may be issued while later layers are still arriving (section 5.2, step 2 of
- * the protocol).  With BZ_RUN_NOWAIT it returns BZ_ENOTREADY instead if any layer of [a,b) is not
+ * instance's cache.  The compute stream waits on layer i's ingest before it runs layer i, so the
+ * call may be issued while later layers are still arriving (section 5.2, step 2 of the protocol).
+ * The paper gates at layer granularity; here, for a layer still in flight that was requested with
+ * bz_load_layer or bz_load_layer_from_device, each stage waits only for the tensors it reads (QKV
+ * group before the first norm, wo and the second norm's gain before the output projection, gate/up
+ * before the MLP, the whole layer before the down projection): the last layer's attention runs
+ * while its MLP weights arrive.  A sharded layer is waited for as a whole.  With BZ_RUN_NOWAIT it returns BZ_ENOTREADY instead if any layer of [a,b) is not
  * resident yet.  Results do not depend on a, b, the frontier or timing: running [a,k) then [k,b)
  * (on this or another instance holding the same weights) is bit-identical to running [a,b). */
 int bz_run_layers(bz_instance* inst, int a, int b, const bz_batch* batch, void* hidden, int flags);

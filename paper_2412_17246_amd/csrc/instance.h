@@ -58,7 +58,12 @@ struct bz_instance {
     unsigned char* wsp = nullptr;
     bool own_weights = false, own_kv = false, own_ws = false;
     std::vector<int> state;
-    std::vector<hipEvent_t> ev;
+    std::vector<hipEvent_t> ev;                  // layer l is complete
+    // A layer copied in blob order also records an event when each group of tensors that one stage of
+    // the layer needs has landed: [3l] QKV group (g1, wq, wk, wv), [3l+1] wo and g2, [3l+2] wg and wu;
+    // the down projection waits for ev[l].  parts_valid[l] says whether the current load recorded them.
+    std::vector<hipEvent_t> ev_part;
+    std::vector<char> parts_valid;
     hipEvent_t t0 = nullptr;
     bool clock_started = false;
     bz::KvSlots* slots = nullptr;

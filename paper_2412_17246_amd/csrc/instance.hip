@@ -200,11 +200,20 @@ int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpy
     const size_t chunk = I->cfg.chunk_bytes > 0 ? (size_t)I->cfg.chunk_bytes : ((size_t)32 << 20);
     unsigned char* dst = layer_ptr(I, layer);
     const unsigned char* s = static_cast<const unsigned char*>(src);
-    for (size_t off = 0; off < n; off += chunk) {
-        const size_t m = n - off < chunk ? n - off : chunk;
-        HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy));
+    // The blob goes over in the order the layer consumes it, with an event behind each group of
+    // tensors, so that the layer's first stages can run while its MLP weights are still arriving.
+    const size_t ends[4] = {I->lay.wo, I->lay.wg, I->lay.wd, n};
+    size_t off = 0;
+    for (int part = 0; part < 4; ++part) {
+        while (off < ends[part]) {
+            const size_t left = ends[part] - off;
+            const size_t m = left < chunk ? left : chunk;
+            HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy));
+            off += m;
+        }
+        HIP_TRY(hipEventRecord(part < 3 ? I->ev_part[3 * layer + part] : I->ev[layer], I->copy));
     }
-    HIP_TRY(hipEventRecord(I->ev[layer], I->copy));
+    I->parts_valid[layer] = 1;
     I->state[layer] = kLoading;
     I->stats.bytes_ingested += n;
     I->stats.layers_requested += 1;
@@ -271,6 +280,7 @@ int bz_destroy(bz_instance* I) {
         if (I->compute) (void)hipStreamSynchronize(I->compute);
         if (I->copy) (void)hipStreamSynchronize(I->copy);
         for (hipEvent_t e : I->ev) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : I->ev_part) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : I->ev_pool) (void)hipEventDestroy(e);
         for (hipStream_t q : I->shard_streams) { (void)hipStreamSynchronize(q); (void)hipStreamDestroy(q); }
         for (hipEvent_t e : I->shard_events) (void)hipEventDestroy(e);
@@ -301,6 +311,7 @@ int bz_create(const bz_config* cfg, bz_instance** out) {
     ws_layout(cfg, &I->ws);
     I->dry = (cfg->flags & BZ_FLAG_DRY_RUN) != 0;
     I->state.assign(cfg->n_layers, kNone);
+    I->parts_valid.assign(cfg->n_layers, 0);
     I->slots = new KvSlots(cfg->max_seqs, cfg->kv_tokens);
     memset(&I->stats, 0, sizeof I->stats);
     if (I->dry) {
@@ -331,6 +342,8 @@ int bz_create(const bz_config* cfg, bz_instance** out) {
     } else { HIP_TRY_C(hipMalloc((void**)&I->wsp, I->sz.workspace_bytes)); I->own_ws = true; }
     I->ev.assign(cfg->n_layers, nullptr);
     for (int l = 0; l < cfg->n_layers; ++l) HIP_TRY_C(hipEventCreate(&I->ev[l]));
+    I->ev_part.assign((size_t)3 * cfg->n_layers, nullptr);
+    for (size_t k = 0; k < I->ev_part.size(); ++k) HIP_TRY_C(hipEventCreateWithFlags(&I->ev_part[k], hipEventDisableTiming));
     HIP_TRY_C(hipEventCreate(&I->t0));
     {   // rotary table: angle = pos * base^(-2j/d) in float64, stored as (cos, sin) floats
         const int d = cfg->head_dim, half = d / 2;
@@ -422,6 +435,7 @@ int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int
         HIP_TRY(hipStreamWaitEvent(I->copy, I->shard_events[q], 0));
     }
     HIP_TRY(hipEventRecord(I->ev[layer], I->copy));      // fires when every shard has landed
+    I->parts_valid[layer] = 0;                            // shards land in no particular order
     I->state[layer] = kLoading;
     I->stats.bytes_ingested += I->sz.layer_bytes;
     I->stats.layers_requested += 1;
@@ -433,6 +447,7 @@ int bz_unload_layer(bz_instance* I, int layer) {
     int rc = bz_sync(I);
     if (rc) return rc;
     I->state[layer] = kNone;
+    I->parts_valid[layer] = 0;
     return BZ_OK;
 }
 
@@ -704,7 +719,11 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
 
     int pending_down = 0;        // split-K slices of the previous layer's down projection still to be folded into x
     for (int l = a; l < b; ++l) {
-        if (I->state[l] != kResident) HIP_TRY(hipStreamWaitEvent(st, I->ev[l], 0));
+        // a layer still on its way gates each stage on the tensors that stage reads (or, when it was
+        // not copied in blob order, everything on the whole layer)
+        const bool gated = I->state[l] != kResident;
+        const bool by_part = gated && I->parts_valid[l];
+        if (gated) HIP_TRY(hipStreamWaitEvent(st, by_part ? I->ev_part[3 * l] : I->ev[l], 0));
         const unsigned char* wl = layer_ptr(I, l);
         const bf16* g1 = (const bf16*)(wl + I->lay.g1);
         const bf16* wqkv = (const bf16*)(wl + I->lay.wq);
@@ -737,14 +756,17 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
             launch_attn_decode(qkv, attn, partial, bv, kvv, sh.Hq, st);
         }
         int ks_o = 0;
+        if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 1], 0));
         { ProfScope p(I, BZ_K_GEMM_O, 2.0 * T * sh.H * qd, (2.0 * T * sh.H + (double)T * qd) * e + 2.0 * sh.H * qd);
           ks_o = launch_gemm_partial(1, attn, wo, T, sh.H, qd, gws, gwsb, st);
           if (ks_o == 0) launch_gemm(1, attn, wo, x, x, T, sh.H, qd, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
           if (ks_o > 0) launch_reduce_residual_rmsnorm(x, gws, ks_o, g2, normed, T, sh.H, I->cfg.rms_eps, st);
           else launch_rmsnorm(x, g2, normed, T, sh.H, I->cfg.rms_eps, st); }
+        if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 2], 0));
         { ProfScope p(I, BZ_K_GEMM_GATEUP, 4.0 * T * sh.F * sh.H, ((double)T * sh.H + (double)T * sh.F) * e + 4.0 * sh.F * sh.H);
           launch_gemm(2, normed, wgu, nullptr, act, T, sh.F, sh.H, gws, gwsb, st); }
+        if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev[l], 0));
         { ProfScope p(I, BZ_K_GEMM_DOWN, 2.0 * T * sh.H * sh.F, (2.0 * T * sh.H + (double)T * sh.F) * e + 2.0 * sh.H * sh.F);
           pending_down = launch_gemm_partial(1, act, wd, T, sh.H, sh.F, gws, gwsb, st);
           if (pending_down == 0) launch_gemm(1, act, wd, x, x, T, sh.H, sh.F, gws, gwsb, st); }

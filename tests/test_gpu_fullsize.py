@@ -112,3 +112,32 @@ def test_8b_gqa_decode_step_full_batch(torch):
     assert err <= U.BF16_TOL, err
     for i in (int(np.argmin(lens)), int(np.argmax(lens))):       # shortest and longest cache on their own
         assert U.rel_err(got[i:i + 1], want[i:i + 1]) <= U.BF16_TOL
+
+
+def test_7b_layer_run_enqueued_while_its_weights_arrive(torch):
+    """run_layers is issued right behind load_layer, while the 405 MB of the layer are on their way: the
+    stages wait for the tensor groups they read, and the output has the bits of a run on the resident
+    layer."""
+    base = W.CONFIGS["7b"]
+    s = _one_layer_shape(base)
+    lens = [211, 122]
+    T = sum(lens)
+    inst = U.make_instance(s, max_seqs=2, max_seq_len=256, max_tokens=T, kv_tokens=512)
+    for i, n in enumerate(lens):
+        inst.kv_reserve(i, n)
+    blob = inst.pinned_blob(inst.pack_layer(W.layer_weights_bits(base, 3)))
+    xbits = W.hidden_bits(base, T, step=11)
+    x1, x2 = U.to_device(xbits, False), U.to_device(xbits, False)
+    batch = inst.batch([0, lens[0], T], [0, 1], [0, 0])
+    torch.cuda.synchronize()
+    inst.load_layer(0, blob)
+    inst.run_layers(0, 1, batch, x1)
+    in_flight = not inst.layer_ready(0)
+    inst.sync()
+    assert inst.layer_ready(0) and inst.frontier() == 1
+    inst.run_layers(0, 1, batch, x2)          # same inputs, same cache positions, layer resident
+    inst.sync()
+    assert in_flight, "the layer had landed before the run was enqueued: the test did not exercise the gating"
+    assert torch.equal(x1.view(torch.int16), x2.view(torch.int16))
+    assert np.array_equal(inst.readback_layer(0), blob.numpy())
+    inst.close()
