@@ -263,6 +263,9 @@ def run_decode(args, torch, Instance):
     B = args.requests if args.requests != 8 else 64
     lo, hi = (512, 4096) if base.name == "70b" else (256, 4096)
     lens = W.uniform_lengths(base.seed, B, lo, hi)
+    if args.fixed_len:                    # every cache the same length (no short sequences, no ragged last chunks)
+        lens = np.full(B, args.fixed_len, dtype=np.int64)
+        lo = hi = args.fixed_len
     n_steps = args.steps + args.warmup + 4
     stream = torch.cuda.Stream()
     gen = torch.Generator(device="cuda")
@@ -537,7 +540,7 @@ def main() -> int:
     ap.add_argument("--shape", default="7b", choices=list(W.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the shape (debugging)")
     ap.add_argument("--requests", type=int, default=8)
-    ap.add_argument("--fixed-len", type=int, default=0, help="prefill_stream: every request has this many tokens")
+    ap.add_argument("--fixed-len", type=int, default=0, help="prefill_stream: every request has this many tokens; decode: every cache has this length")
     ap.add_argument("--distinct-blobs", type=int, default=0, help="prefill_stream: feed layer i from pinned blob i mod m")
     ap.add_argument("--shards", type=int, default=1, help="prefill_stream: ingest every layer as this many parallel shards")
     ap.add_argument("--split", type=int, default=0, help="decode: also run a live split at this layer and compare bits")

@@ -235,7 +235,10 @@ int bz_batch_create(const bz_batch_desc* desc, bz_batch** out);
 int bz_batch_destroy(bz_batch* batch);
 int bz_batch_tokens(const bz_batch* batch);
 /* For a batch in which every sequence has exactly one new token: enqueue, on `inst`'s compute
- * stream, kv_len_before[s] += 1 for all s — the next decode step of the same sequences. */
+ * stream, kv_len_before[s] += 1 for all s — the next decode step of the same sequences.  The
+ * batch's list of cache chunks is rebuilt on the device in the same step; it has room for 16384
+ * positions of growth per sequence since bz_batch_create, beyond which the call returns
+ * BZ_ECAPACITY and changes nothing (build a new batch). */
 int bz_batch_advance(bz_instance* inst, bz_batch* batch);
 
 /* ---- execution ------------------------------------------------------------------------------ */

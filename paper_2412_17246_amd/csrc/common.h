@@ -123,6 +123,14 @@ struct BatchView {
     const int32_t* decode_seqs;    // [n_decode] sequence indices with exactly one new token
     int n_decode;
     int decode_chunks;             // upper bound on ceil((kv_before+1)/kDecodeChunk) over decode seqs
+    // One entry (two int4) per (decode sequence, chunk of its cache) that exists now, sequence by
+    // sequence: (sequence index, KV slot, index into decode_seqs, chunks of this sequence), (index of
+    // the sequence's first entry, 0, 0, 0).  The decode attention runs n_decode_work * Hkv workgroups;
+    // workgroup b reads entry b / Hkv, which belongs to the right sequence, and takes
+    // (kv head, chunk) = divmod(b - Hkv * first, chunks): a sequence's kv heads one after the other,
+    // each head's chunks in order, which is the order the cache lies in memory.
+    const int4* decode_work;
+    int n_decode_work;
 };
 
 constexpr int kPrefillTileQ = 128;   // query rows per prefill-attention workgroup
@@ -155,7 +163,10 @@ void launch_attn_decode(const act_t* qkv, act_t* out, float* partial, const Batc
                         int Hq, hipStream_t st_);
 void launch_kv_scatter(const act_t* src_k, const act_t* src_v, const KvView& kv, int slot, int pos0, int n,
                        bool to_cache, act_t* dst_k, act_t* dst_v, hipStream_t st);
-void launch_batch_advance(int32_t* kv_before, int B, hipStream_t st);
+// kv_before[s] += 1 for every sequence, then the decode work list is rebuilt for the new lengths
+// (at most `capacity` entries are written; the caller has checked that they suffice)
+void launch_batch_advance(int32_t* kv_before, int B, const int32_t* decode_seqs, const int32_t* seq_slot, int n_decode,
+                          int4* work, int capacity, hipStream_t st);
 
 // floats per (decode sequence, query head, chunk) in the decode partial buffer: d outputs, max, sum
 __host__ __device__ inline int decode_partial_stride(int d) { return d + 2; }

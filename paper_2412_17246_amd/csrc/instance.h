@@ -42,6 +42,8 @@ struct bz_batch {
     void* dev = nullptr;              // one allocation holding all device arrays
     int32_t *d_q_start = nullptr, *d_seq_slot = nullptr, *d_kv_before = nullptr, *d_token_seq = nullptr,
             *d_items = nullptr, *d_decode = nullptr;
+    int4* d_work = nullptr;           // decode work list (see BatchView), room for work_capacity entries
+    int work_capacity = 0;
 };
 
 struct bz_instance {

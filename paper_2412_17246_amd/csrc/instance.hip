@@ -141,9 +141,14 @@ BatchView batch_view(const bz_batch* b) {
     v.n_prefill_items = b->n_prefill_items;
     v.decode_seqs = b->d_decode;
     v.n_decode = b->n_decode;
-    int mx = 0;
-    for (int s : b->decode_seqs) mx = mx > b->kv_before[s] + 1 ? mx : b->kv_before[s] + 1;
+    int mx = 0, work = 0;
+    for (int s : b->decode_seqs) {
+        mx = mx > b->kv_before[s] + 1 ? mx : b->kv_before[s] + 1;
+        work += (b->kv_before[s] + 1 + kDecodeChunk - 1) / kDecodeChunk;
+    }
     v.decode_chunks = (mx + kDecodeChunk - 1) / kDecodeChunk;
+    v.decode_work = b->d_work;
+    v.n_decode_work = work;             // the device list was built for these same lengths
     return v;
 }
 
@@ -645,8 +650,23 @@ int bz_batch_create(const bz_batch_desc* d, bz_batch** out) {
     b->n_prefill_items = (int)its.size();
     b->n_decode = (int)b->decode_seqs.size();
 
+    // decode work list: one entry per chunk of every decode sequence's cache (the new token included), with
+    // room for kWorkGrowth more chunks per sequence as bz_batch_advance lengthens the caches
+    std::vector<int32_t> work;
+    for (int di = 0; di < b->n_decode; ++di) {
+        const int s = b->decode_seqs[di];
+        const int n = (b->kv_before[s] + 1 + kDecodeChunk - 1) / kDecodeChunk;
+        const int first = (int)(work.size() / 8);
+        for (int c = 0; c < n; ++c) {
+            const int32_t entry[8] = {s, b->seq_slot[s], di, n, first, 0, 0, 0};
+            work.insert(work.end(), entry, entry + 8);
+        }
+    }
+    constexpr int kWorkGrowth = 64;
+    b->work_capacity = (int)(work.size() / 8) + kWorkGrowth * b->n_decode;
     const size_t n_i32 = (size_t)(B + 1) + B + B + T + items.size() + b->decode_seqs.size();
-    hipError_t e = hipMalloc(&b->dev, n_i32 * 4 + 64);
+    const size_t work_at = (n_i32 * 4 + 31) / 32 * 32;              // 32-byte entries
+    hipError_t e = hipMalloc(&b->dev, work_at + (size_t)b->work_capacity * 32 + 64);
     if (e != hipSuccess) { hip_fail(e, "hipMalloc(batch)"); delete b; return BZ_EHIP; }
     std::vector<int32_t> host;
     host.reserve(n_i32);
@@ -659,6 +679,8 @@ int bz_batch_create(const bz_batch_desc* d, bz_batch** out) {
     b->d_items = put(items);
     b->d_decode = put(b->decode_seqs);
     e = hipMemcpy(b->dev, host.data(), host.size() * 4, hipMemcpyHostToDevice);
+    b->d_work = reinterpret_cast<int4*>(static_cast<unsigned char*>(b->dev) + work_at);
+    if (e == hipSuccess && !work.empty()) e = hipMemcpy(b->d_work, work.data(), work.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { hip_fail(e, "hipMemcpy(batch)"); bz_batch_destroy(b); return BZ_EHIP; }
     *out = b;
     return BZ_OK;
@@ -670,7 +692,11 @@ int bz_batch_advance(bz_instance* I, bz_batch* b) {
     if (!I || !b) return BZ_EINVAL;
     if (!b->all_decode) return BZ_ESTATE;
     if (I->dry) return BZ_ESTATE;
-    launch_batch_advance(b->d_kv_before, b->B, I->compute);
+    long long work = 0;                  // entries of the work list after this step
+    for (int s : b->decode_seqs) work += (b->kv_before[s] + 2 + kDecodeChunk - 1) / kDecodeChunk;
+    if (work > b->work_capacity) return BZ_ECAPACITY;
+    launch_batch_advance(b->d_kv_before, b->B, b->d_decode, b->d_seq_slot, b->n_decode, b->d_work, b->work_capacity,
+                         I->compute);
     HIP_TRY(hipGetLastError());
     for (auto& v : b->kv_before) v += 1;
     return BZ_OK;

@@ -13,6 +13,13 @@
 
 namespace bz {
 
+// Loads of cache contents that are read once per step (decode attention): non-temporal, so that the
+// stream does not push through the caches what nobody will read again; on this chip a streaming read
+// of that kind runs about a quarter faster than a default one.
+#ifndef BZ_STREAM_LOAD
+#define BZ_STREAM_LOAD(ptr) __builtin_nontemporal_load(ptr)
+#endif
+
 constexpr float kLog2e = 1.4426950408889634f;
 
 #ifndef BZ_FP32_DEBUG
@@ -313,13 +320,17 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
     __shared__ float wsum[4][kDecodeMaxG];
     __shared__ float osh[4][kDecodeMaxG][D];
 
-    const int chunk = blockIdx.x, kvh = blockIdx.y, di = blockIdx.z;
-    const int s = bv.decode_seqs[di];
+    // the work list names only chunks that exist, and brings the sequence's slot along: everything else
+    // hangs off one more level of loads (see BatchView for the order of workgroups)
+    const int e = blockIdx.x / kv.Hkv;
+    const int4 item = bv.decode_work[2 * e], item2 = bv.decode_work[2 * e + 1];
+    const int s = item.x, slot = item.y, di = item.z;
+    const int rest = blockIdx.x - kv.Hkv * item2.x;          // position among this sequence's (kv head, chunk) pairs
+    const int kvh = rest / item.w, chunk = rest - kvh * item.w;
     const int len = bv.kv_before[s] + 1;
     const int c0 = chunk * CH;
     if (c0 >= len) return;
     const int t = bv.q_start[s];
-    const int slot = bv.seq_slot[s];
     const int Hkv = kv.Hkv, cap = kv.slot_cap[slot];
     const size_t head_base = (size_t)kv.slot_off[slot] * Hkv * D + (size_t)kvh * cap * D;
     const bf16* Kc = kv.k + head_base;
@@ -345,7 +356,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                kf[rb][ks] = *reinterpret_cast<const bf16x8*>(Kc + boff[rb] + ((ks * 2 + lh) * 32 + lq) * 8);
+                kf[rb][ks] = BZ_STREAM_LOAD(reinterpret_cast<const bf16x8*>(Kc + boff[rb] + ((ks * 2 + lh) * 32 + lq) * 8));
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -353,7 +364,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
                     vf[rb][tt][db] =
-                        *reinterpret_cast<const bf16x8*>(Vc + boff[rb] + ((2 * tt + lh) * D + db * 32 + lq) * 8);
+                        BZ_STREAM_LOAD(reinterpret_cast<const bf16x8*>(Vc + boff[rb] + ((2 * tt + lh) * D + db * 32 + lq) * 8));
         bf16x8 qf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -466,13 +477,17 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
     __shared__ float osh[4][G][D];
     __shared__ float qs[G][D];
 
-    const int chunk = blockIdx.x, kvh = blockIdx.y, di = blockIdx.z;
-    const int s = bv.decode_seqs[di];
+    // the work list names only chunks that exist, and brings the sequence's slot along: everything else
+    // hangs off one more level of loads (see BatchView for the order of workgroups)
+    const int e = blockIdx.x / kv.Hkv;
+    const int4 item = bv.decode_work[2 * e], item2 = bv.decode_work[2 * e + 1];
+    const int s = item.x, slot = item.y, di = item.z;
+    const int rest = blockIdx.x - kv.Hkv * item2.x;          // position among this sequence's (kv head, chunk) pairs
+    const int kvh = rest / item.w, chunk = rest - kvh * item.w;
     const int len = bv.kv_before[s] + 1;
     const int c0 = chunk * CH;
     if (c0 >= len) return;
     const int t = bv.q_start[s];
-    const int slot = bv.seq_slot[s];
     const int Hkv = kv.Hkv, cap = kv.slot_cap[slot];
     const size_t head_base = (size_t)kv.slot_off[slot] * Hkv * D + (size_t)kvh * cap * D;
     const float* Kc = kv.k + head_base;
@@ -624,7 +639,7 @@ template <int D>
 static void launch_decode_d(const act_t* qkv, act_t* out, float* partial, const BatchView& bv, const KvView& kv,
                             int Hq, hipStream_t st) {
     const float scale_log2 = kLog2e / sqrtf((float)D);
-    const dim3 grid(bv.decode_chunks, kv.Hkv, bv.n_decode);
+    const dim3 grid(bv.n_decode_work * kv.Hkv);
     const int G = Hq / kv.Hkv;                      // 1, 2, 4 or 8: checked when the instance is created
 #ifndef BZ_FP32_DEBUG
     hipLaunchKernelGGL(attn_decode_kernel<D>, grid, dim3(256), 0, st, qkv, partial, bv, kv, Hq, G, scale_log2);

@@ -374,13 +374,51 @@ void launch_kv_scatter(const act_t* src_k, const act_t* src_v, const KvView& kv,
                        to_cache ? 1 : 0, dst_k, dst_v);
 }
 
-__global__ void batch_advance_kernel(int32_t* kv_before, int B) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < B) kv_before[i] += 1;
+// One workgroup: moves every sequence one position on, then lists the (sequence, chunk) pairs the decode
+// attention has to visit at the new lengths, sequence by sequence (an exclusive scan over chunk counts).
+__global__ __launch_bounds__(256) void batch_advance_kernel(int32_t* kv_before, int B, const int32_t* __restrict__ decode_seqs,
+                                                            const int32_t* __restrict__ seq_slot, int n_decode, int4* work,
+                                                            int capacity) {
+    __shared__ int scan[256];
+    __shared__ int base;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < B; i += 256) kv_before[i] += 1;
+    if (tid == 0) base = 0;
+    __syncthreads();
+    for (int d0 = 0; d0 < n_decode; d0 += 256) {
+        const int di = d0 + tid;
+        int s = 0, n = 0;
+        if (di < n_decode) {
+            s = decode_seqs[di];
+            n = (kv_before[s] + 1 + kDecodeChunk - 1) / kDecodeChunk;
+        }
+        scan[tid] = n;
+        __syncthreads();
+        for (int step = 1; step < 256; step <<= 1) {
+            const int add = tid >= step ? scan[tid - step] : 0;
+            __syncthreads();
+            scan[tid] += add;
+            __syncthreads();
+        }
+        const int at = base + scan[tid] - n;
+        if (n > 0) {
+            const int slot = seq_slot[s];
+            for (int c = 0; c < n; ++c)
+                if (at + c < capacity) {
+                    work[2 * (at + c)] = make_int4(s, slot, di, n);
+                    work[2 * (at + c) + 1] = make_int4(at, 0, 0, 0);
+                }
+        }
+        __syncthreads();
+        if (tid == 255) base += scan[255];
+        __syncthreads();
+    }
 }
 
-void launch_batch_advance(int32_t* kv_before, int B, hipStream_t st) {
-    hipLaunchKernelGGL(batch_advance_kernel, dim3((B + 255) / 256), dim3(256), 0, st, kv_before, B);
+void launch_batch_advance(int32_t* kv_before, int B, const int32_t* decode_seqs, const int32_t* seq_slot, int n_decode,
+                          int4* work, int capacity, hipStream_t st) {
+    hipLaunchKernelGGL(batch_advance_kernel, dim3(1), dim3(256), 0, st, kv_before, B, decode_seqs, seq_slot, n_decode, work,
+                       capacity);
 }
 
 }  // namespace bz

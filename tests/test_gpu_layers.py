@@ -363,3 +363,54 @@ def test_gqa_decode_live_split_is_bit_exact_over_steps(torch):
         assert torch.equal(a.view(torch.int16), c.view(torch.int16)), step
     for inst in (whole, tgt, src):
         inst.close()
+
+
+@pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
+def test_decode_steps_across_chunk_boundaries_follow_the_oracle(torch, fp32):
+    """Continuous decode with batch_advance while caches grow past multiples of 256 positions: the list of
+    cache chunks the attention visits is rebuilt on the device every step."""
+    s, os_ = MIX, U.oracle_shape(MIX)
+    lens = [254, 255, 510, 3, 767]
+    B, steps = len(lens), 4
+    inst = U.make_instance(s, max_seqs=B, max_seq_len=1024, max_tokens=B, kv_tokens=sum(lens) + 64 * B, fp32=fp32)
+    bits = {l: W.layer_weights_bits(s, l) for l in range(s.L)}
+    wts = {l: U.oracle_weights(bits[l]) for l in range(s.L)}
+    U.load_all_layers(inst, s)
+    okv = O.OracleKV()
+    for i, n in enumerate(lens):
+        inst.kv_reserve(i, n + steps)
+        for l in range(s.L):
+            kb, vb = W.kv_prefill_bits(s, l, i, n)
+            okv.put(l, i, U.f64(kb), U.f64(vb))
+            if fp32:
+                inst.kv_write(l, i, 0, n, W.f32_from_bf16_bits(kb), W.f32_from_bf16_bits(vb))
+            else:
+                inst.kv_write(l, i, 0, n, kb, vb)
+    batch = inst.batch(list(range(B + 1)), list(range(B)), lens)
+    for step in range(steps):
+        xbits = W.hidden_bits(s, B, step=60 + step)
+        x = U.to_device(xbits, fp32)
+        torch.cuda.synchronize()
+        inst.run_layers(0, s.L, batch, x)
+        inst.batch_advance(batch)
+        inst.sync()
+        want = O.run_layers(os_, wts, 0, s.L, U.f64(xbits),
+                            O.OracleBatch(list(range(B + 1)), list(range(B)), [n + step for n in lens]), okv)
+        got = U.from_device(x)
+        for i in range(B):
+            assert U.rel_err(got[i:i + 1], want[i:i + 1]) <= _tol(fp32), (step, i)
+    inst.close()
+
+
+def test_batch_advance_reports_when_its_chunk_list_is_full(torch):
+    s = TINY
+    inst = U.make_instance(s, max_seqs=1, max_seq_len=64, max_tokens=1, kv_tokens=64)
+    batch = inst.batch([0, 1], [0], [0])
+    room = (1 + 64) * 256 - 1                   # the cache may grow to 65 chunks of 256 positions
+    for _ in range(room):
+        inst.batch_advance(batch)
+    with pytest.raises(Exception) as ei:
+        inst.batch_advance(batch)
+    assert "BZ_ECAPACITY" in str(ei.value)
+    inst.sync()
+    inst.close()
