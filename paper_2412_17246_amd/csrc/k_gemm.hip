@@ -687,36 +687,59 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 // ---------------------------------------------------------------------------------------------
 // Skinny kernel for decode-sized problems (M <= 64 rows): the weights are read from HBM exactly
 // once and that read is the whole cost, so the job is to keep every CU streaming.  Work is cut
-// into 64-feature tiles times KSPLIT slices of K (a function of the shape only); each workgroup
-// streams its weight slice and the matching activation slice through a ring of 16 KiB LDS
-// stages filled by direct global->LDS loads, multiplies with one 32x32x16 MFMA per wave and
+// into tiles of 64 * RB weight rows times KSPLIT slices of K (a function of the shape only); each
+// workgroup streams its weight slice and the matching activation slice through a ring of LDS
+// stages filled by direct global->LDS loads, multiplies with RB 32x32x16 MFMAs per wave and
 // k-step, and writes an fp32 partial tile.  A second kernel adds the slices in slice order and
 // applies the epilogue, so the result is deterministic.
+//
+// RB = 1: 64-row tiles, four 16 KiB stages, two workgroups per CU: short streams (small matrices),
+// where many small workgroups start and finish faster.
+// RB = 2: 128-row tiles, five 24 KiB stages, one workgroup per CU: long streams.  Every tile re-reads
+// the activations from L2, which costs about a tenth of the time at 64 rows; twice the rows halve
+// that, and the deeper ring keeps 64 KiB of weights in flight per CU instead of 48.  Measured against
+// RB = 1 on the decode shapes (64 rows): 8B-GQA down projection 31.4 -> 28.0 us, gate/up unchanged;
+// 70B qkv 40.9 -> 37.1, o 36.1 -> 37.8, gate/up 185 -> 168, down 96.5 -> 78.5 us.  (Three stages and
+// two workgroups per CU win on some of these shapes and lose on others.)
 // ---------------------------------------------------------------------------------------------
-constexpr int kSkStage = (64 + 64) * kBK * (int)sizeof(bf16);    // 16384
-#ifndef BZ_SK_STAGES
-#define BZ_SK_STAGES 4
+template <int RB> struct SkCfg {
+    static constexpr int kStage = (64 + 64 * RB) * kBK * (int)sizeof(bf16);   // activations 8 KiB, weights 8 KiB * RB
+#ifndef BZ_SK2_STAGES
+#define BZ_SK2_STAGES 5
 #endif
-constexpr int kSkStages = BZ_SK_STAGES;
+    static constexpr int kStages = RB == 1 ? 4 : BZ_SK2_STAGES;
+    static constexpr int kLds = kStage * kStages;
+    static constexpr int kPerCu = kLds * 2 <= 160 * 1024 ? 2 : 1;
+    static constexpr int kSlots = 256 * kPerCu;                               // workgroups the chip holds at a time
+};
 #ifndef BZ_SK_STREAM_MIB
 #define BZ_SK_STREAM_MIB 64
 #endif
-constexpr size_t kSkStreamBytes = (size_t)BZ_SK_STREAM_MIB << 20;   // weight matrices from this size on are read non-temporally    // 16 KiB each; two workgroups share a CU's 160 KiB
+// Weight matrices from this size on count as long streams: RB = 2, and loads with the non-temporal cache
+// policy (read once per step; streamed that way a long read runs faster - gate/up of the 8B shape -6 % -
+// a short one does not or gets slower).
+constexpr size_t kSkStreamBytes = (size_t)BZ_SK_STREAM_MIB << 20;
 
-// GU (gate/up projection): a tile is 32 gate features (weight rows n0..n0+31) and the 32 matching up
+// vmcnt(n) lgkmcnt(0), n < 64
+__device__ __forceinline__ constexpr int sk_wait(int n) { return ((n >> 4) << 14) | 0x0070 | (n & 15); }
+
+// GU (gate/up projection): a tile is 32 * RB gate features (weight rows n0..) and the matching up
 // features (rows N + n0..), so that with a single k-slice the workgroup holds both factors of
 // silu(gate) * up and writes the activation itself (C != nullptr) instead of partial sums.
-// NT: the weight loads carry the non-temporal cache policy.  Weights are read once per step; streamed
-// that way a long read runs faster (measured: gate/up of the 8B shape -6 %, down -2.5 %), a short one
-// (under about 64 MiB of weights) does not or gets slower, so the launcher decides by size.
-template <bool GU, bool NT>
-__global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
-                                                             float* __restrict__ partial, bf16* __restrict__ C, int M,
-                                                             int Nrows, int K, int n_tiles, int kt_per_split, int rows) {
+// NT: the weight loads carry the non-temporal cache policy.
+template <bool GU, bool NT, int RB>
+__global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(const bf16* __restrict__ X,
+                                                                           const bf16* __restrict__ W,
+                                                                           float* __restrict__ partial,
+                                                                           bf16* __restrict__ C, int M, int Nrows, int K,
+                                                                           int n_tiles, int kt_per_split, int rows) {
+    constexpr int kStage = SkCfg<RB>::kStage, kStages = SkCfg<RB>::kStages;
+    constexpr int LPS = 2 + 2 * RB;                   // loads per wave and stage
+    constexpr int HALF = 32 * RB;                     // rows per wave along the features (GU: rows per factor)
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
     const int tile_n = blockIdx.x % n_tiles, split = blockIdx.x / n_tiles;
-    // `rows` <= 64 weight rows of the 64 the tile has room for are real (GU: rows / 2 of each factor); the
-    // launcher picks it so that the grid fills the chip's workgroup slots evenly
+    // `rows` <= 64 * RB weight rows of those the tile has room for are real (GU: rows / 2 of each factor);
+    // the launcher picks it so that the grid fills the chip's workgroup slots evenly
     const int tr = GU ? rows >> 1 : rows;             // real rows per factor (GU) or per tile
     const int n0 = tile_n * tr;
     const int Nh = Nrows >> 1;                        // GU: features per factor
@@ -730,75 +753,86 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restr
     const int lrow = lane & 31, lk = lane >> 5;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-    // loader: chunks 0..7 hold the activation rows, 8..15 the weight rows; this wave fills chunks
-    // 2*wave, 2*wave+1 of each
-    uint32_t x_src[2], w_src[2];
+    // loader: 1 KiB chunks of 8 rows; chunks 0..7 of a stage hold the activation rows, the 8 * RB after
+    // them the weight rows; this wave fills chunks 2*wave, 2*wave+1 of the former and 2*RB of the latter
+    uint32_t x_src[2], w_src[2 * RB];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int row = (wave * 2 + j) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ swz(row);
         int xr = row;
         if (xr > M - 1) xr = M - 1;
-        x_src[j] = ((uint32_t)xr * (uint32_t)K + c * 8) * 2u;
+        x_src[j] = ((uint32_t)xr * (uint32_t)K + ((lane & 7) ^ swz(row)) * 8) * 2u;
+    }
+#pragma unroll
+    for (int j = 0; j < 2 * RB; ++j) {
+        const int row = (wave * 2 * RB + j) * 8 + (lane >> 3);
         int wr;
         if (GU) {                                      // rows past the real ones re-read the tile's last row
-            int r = row & 31;
+            int r = row % HALF;
             if (r > tr - 1) r = tr - 1;
             int f = n0 + r;
             if (f > Nh - 1) f = Nh - 1;
-            wr = (row >> 5) * Nh + f;
+            wr = (row / HALF) * Nh + f;
         } else {
             wr = n0 + (row < tr ? row : tr - 1);
             if (wr > Nrows - 1) wr = Nrows - 1;
         }
-        w_src[j] = ((uint32_t)wr * (uint32_t)K + c * 8) * 2u;
+        w_src[j] = ((uint32_t)wr * (uint32_t)K + ((lane & 7) ^ swz(row)) * 8) * 2u;
     }
     auto issue = [&](int kt, int stage) {
         const char* xk = reinterpret_cast<const char*>(X + (size_t)kt * kBK);
         const char* wk = reinterpret_cast<const char*>(W + (size_t)kt * kBK);
-        unsigned char* sx = smem_raw + stage * kSkStage + wave_u * 2 * 1024;
+        unsigned char* sb = smem_raw + stage * kStage;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(xk + x_src[j]), (lptr_t)(sx + j * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(wk + w_src[j]), (lptr_t)(sx + 8192 + j * 1024), 16, 0, NT ? 2 : 0);
-        }
+        for (int j = 0; j < 2; ++j)
+            __builtin_amdgcn_global_load_lds((gptr_t)(xk + x_src[j]), (lptr_t)(sb + (wave_u * 2 + j) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 2 * RB; ++j)
+            __builtin_amdgcn_global_load_lds((gptr_t)(wk + w_src[j]), (lptr_t)(sb + 8192 + (wave_u * 2 * RB + j) * 1024), 16,
+                                             0, NT ? 2 : 0);
     };
 
-    f32x16 acc;
+    f32x16 acc[RB];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int b = 0; b < RB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
     const int sw = swz(lrow);
     const int x_off = (wt * 32 + lrow) * 128;
-    const int w_off = 8192 + (wf * 32 + lrow) * 128;
+    const int w_off = 8192 + (wf * HALF + lrow) * 128;
 
-    // prologue: up to kSkStages - 1 tiles in flight
+    // prologue: up to kStages - 1 tiles in flight
 #pragma unroll
-    for (int t = 0; t < kSkStages - 1; ++t)
+    for (int t = 0; t < kStages - 1; ++t)
         if (n > t) issue(kt0 + t, t);
-    int cur = 0, nxt = kSkStages - 1;                // stage of tile i; stage the tile requested next goes to
+    int cur = 0, nxt = kStages - 1;                  // stage of tile i; stage the tile requested next goes to
     for (int i = 0; i < n; ++i) {
-        // tile i must have landed; the tiles requested after it (4 loads each) may still be in flight
-        const int later = (n - 1 - i < kSkStages - 2) ? n - 1 - i : kSkStages - 2;
-        if (later >= 3) __builtin_amdgcn_s_waitcnt(0x007C);        // vmcnt(12) lgkmcnt(0)
-        else if (later == 2) __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
-        else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0074);   // vmcnt(4) lgkmcnt(0)
-        else __builtin_amdgcn_s_waitcnt(0x0070);                   // vmcnt(0) lgkmcnt(0)
+        // tile i must have landed; the tiles requested after it (LPS loads each) may still be in flight
+        const int later = (n - 1 - i < kStages - 2) ? n - 1 - i : kStages - 2;
+        if (later >= 4) __builtin_amdgcn_s_waitcnt(sk_wait(4 * LPS));
+        else if (later == 3) __builtin_amdgcn_s_waitcnt(sk_wait(3 * LPS));
+        else if (later == 2) __builtin_amdgcn_s_waitcnt(sk_wait(2 * LPS));
+        else if (later == 1) __builtin_amdgcn_s_waitcnt(sk_wait(LPS));
+        else __builtin_amdgcn_s_waitcnt(sk_wait(0));
         __builtin_amdgcn_s_barrier();                              // everyone's part landed; the stage of tile i-1 is free
         __builtin_amdgcn_sched_barrier(0);
-        if (i + kSkStages - 1 < n) issue(kt0 + i + kSkStages - 1, nxt);
-        const unsigned char* st = smem_raw + cur * kSkStage;
+        if (i + kStages - 1 < n) issue(kt0 + i + kStages - 1, nxt);
+        const unsigned char* st = smem_raw + cur * kStage;
         nxt = cur;
-        cur = (cur + 1 == kSkStages) ? 0 : cur + 1;
+        cur = (cur + 1 == kStages) ? 0 : cur + 1;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int ko = ((ks * 2 + lk) ^ sw) * 16;
             const bf16x8 xf = *reinterpret_cast<const bf16x8*>(st + x_off + ko);
-            const bf16x8 wfr = *reinterpret_cast<const bf16x8*>(st + w_off + ko);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr, xf, acc, 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < RB; ++b) {
+                const bf16x8 wfr = *reinterpret_cast<const bf16x8*>(st + w_off + b * 32 * 128 + ko);
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr, xf, acc[b], 0, 0, 0);
+            }
         }
     }
 
-    // lane holds token wt*32 + lane%32 and, of its wave's 32 features, 8g + 4*(lane/32) + 0..3
+    // lane holds token wt*32 + lane%32 and, of block b of its wave's rows, features 8g + 4*(lane/32) + 0..3
     const int m = wt * 32 + lrow;
     if (GU && C != nullptr) {
         // the up-factor waves hand their accumulators to the gate-factor waves (same lane, same
@@ -807,36 +841,44 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(const bf16* __restr
         __syncthreads();
         if (wf == 1) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) ex[(wt * 16 + r) * 64 + lane] = acc[r];
+            for (int b = 0; b < RB; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ex[((wt * RB + b) * 16 + r) * 64 + lane] = acc[b][r];
         }
         __syncthreads();
         if (wf == 0 && m < M) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int nn = n0 + 8 * g + 4 * lk;
-                if (8 * g + 4 * lk < tr && nn < Nh) {
-                    bf16x4 w4;
+            for (int b = 0; b < RB; ++b)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float o = acc[4 * g + e], u = ex[(wt * 16 + 4 * g + e) * 64 + lane];
-                        w4[e] = (bf16)(o / (1.0f + __expf(-o)) * u);
+                for (int g = 0; g < 4; ++g) {
+                    const int lf = b * 32 + 8 * g + 4 * lk;
+                    const int nn = n0 + lf;
+                    if (lf < tr && nn < Nh) {
+                        bf16x4 w4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float o = acc[b][4 * g + e], u = ex[((wt * RB + b) * 16 + 4 * g + e) * 64 + lane];
+                            w4[e] = (bf16)(o / (1.0f + __expf(-o)) * u);
+                        }
+                        *reinterpret_cast<bf16x4*>(C + (size_t)m * Nh + nn) = w4;
                     }
-                    *reinterpret_cast<bf16x4*>(C + (size_t)m * Nh + nn) = w4;
                 }
-            }
         }
         return;
     }
     if (m < M) {                                       // partial[split][m][n]
         float* prow = partial + ((size_t)split * M + m) * Nrows;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int lf = (GU ? 0 : wf * 32) + 8 * g + 4 * lk;      // feature inside the tile
-            const int f = n0 + lf;
-            const int nn = GU ? wf * Nh + f : f;
-            if (lf < tr && f < (GU ? Nh : Nrows))
-                *reinterpret_cast<float4*>(prow + nn) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
-        }
+        for (int b = 0; b < RB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int lf = (GU ? 0 : wf * HALF) + b * 32 + 8 * g + 4 * lk;      // feature inside the tile (GU: the factor)
+                const int f = n0 + lf;
+                const int nn = GU ? wf * Nh + f : f;
+                if (lf < tr && f < (GU ? Nh : Nrows))
+                    *reinterpret_cast<float4*>(prow + nn) =
+                        make_float4(acc[b][4 * g], acc[b][4 * g + 1], acc[b][4 * g + 2], acc[b][4 * g + 3]);
+            }
     }
 }
 
@@ -875,38 +917,44 @@ __global__ __launch_bounds__(256) void gemm_skinny_epilogue(const float* __restr
 }
 
 struct SkinnyPlan {
-    int n_tiles, kt_per_split, ksplit, rows;
+    int n_tiles, kt_per_split, ksplit, rows, rb;
     size_t ws_bytes;
 };
+
+template <int RB>
+static void skinny_plan_rb(SkinnyPlan& p, int Nrows, int nk) {
+    constexpr int kTile = 64 * RB, kSlots = SkCfg<RB>::kSlots;
+    p.rb = RB;
+    p.n_tiles = (Nrows + kTile - 1) / kTile;
+    int target = kSlots / p.n_tiles;              // aim at filling every workgroup slot once
+    if (target < 1) target = 1;
+    p.kt_per_split = (nk + target - 1) / target;
+    const int min_kt = nk < 4 * RB ? nk : 4 * RB; // keep the ring worth filling
+    if (p.kt_per_split < min_kt) p.kt_per_split = min_kt;
+    p.ksplit = (nk + p.kt_per_split - 1) / p.kt_per_split;
+    // A grid a little short of a multiple of the slots leaves some of them idle for the whole kernel (448
+    // workgroups on 512 slots: an eighth of the chip).  Narrower tiles (down to three quarters of the rows,
+    // in steps of 8) bring the count up to the multiple; narrower than that, the activations would be
+    // re-read by too many tiles.
+    p.rows = kTile;
+    const int total = p.n_tiles * p.ksplit;
+    const int rounds = (total + kSlots - 1) / kSlots;
+    const int want_tiles = rounds * kSlots / p.ksplit;
+    if (want_tiles > p.n_tiles) {
+        const int r = ((Nrows + want_tiles - 1) / want_tiles + 7) / 8 * 8;
+        if (r >= kTile * 3 / 4 && r < kTile) {
+            p.rows = r;
+            p.n_tiles = (Nrows + r - 1) / r;
+        }
+    }
+}
 
 static SkinnyPlan skinny_plan(int M, int N, int K, int mode) {
     SkinnyPlan p;
     const int Nrows = (mode == 2) ? 2 * N : N;
     const int nk = K / kBK;
-    p.n_tiles = (Nrows + 63) / 64;
-    int target = 512 / p.n_tiles;                 // aim at two workgroups per CU
-    if (target < 1) target = 1;
-    p.kt_per_split = (nk + target - 1) / target;
-    const int min_kt = nk < 4 ? nk : 4;           // keep the ring worth filling
-    if (p.kt_per_split < min_kt) p.kt_per_split = min_kt;
-    p.ksplit = (nk + p.kt_per_split - 1) / p.kt_per_split;
-    // The chip holds 512 of these workgroups at a time; a grid a little short of a multiple of that leaves
-    // slots idle for the whole kernel (448 workgroups: an eighth of the chip).  Narrower tiles (down to 48 of
-    // the 64 rows, in steps of 8) bring the count up to the multiple; narrower than that, the activations
-    // would be re-read by too many tiles.
-    p.rows = 64;
-    {
-        const int total = p.n_tiles * p.ksplit;
-        const int rounds = (total + 511) / 512;
-        const int want_tiles = rounds * 512 / p.ksplit;
-        if (want_tiles > p.n_tiles) {
-            int r = ((Nrows + want_tiles - 1) / want_tiles + 7) / 8 * 8;
-            if (r >= 48 && r < 64) {
-                p.rows = r;
-                p.n_tiles = (Nrows + r - 1) / r;
-            }
-        }
-    }
+    if ((size_t)Nrows * K * sizeof(bf16) >= kSkStreamBytes) skinny_plan_rb<2>(p, Nrows, nk);
+    else skinny_plan_rb<1>(p, Nrows, nk);
     p.ws_bytes = (size_t)p.ksplit * M * Nrows * sizeof(float);
     return p;
 }
@@ -932,25 +980,29 @@ static int launch_skinny_partial(int mode, const bf16* a, const bf16* w, bf16* c
                                  hipStream_t st) {
     const SkinnyPlan p = skinny_plan(M, N, K, mode);
     const int Nrows = (mode == 2) ? 2 * N : N;
-    constexpr int LDS = kSkStages * kSkStage;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<false, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<false, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<true, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<true, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<false, false, 1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<1>::kLds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<true, false, 1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<1>::kLds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<false, true, 2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<2>::kLds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<true, true, 2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<2>::kLds);
         attr_set = true;
     }
     const dim3 grid(p.n_tiles * p.ksplit);
-    const bool nt = (size_t)Nrows * K * sizeof(bf16) >= kSkStreamBytes;
     bf16* direct = (mode == 2 && p.ksplit == 1) ? c : nullptr;
-    auto kern = mode == 2 ? (nt ? gemm_skinny_kernel<true, true> : gemm_skinny_kernel<true, false>)
-                          : (nt ? gemm_skinny_kernel<false, true> : gemm_skinny_kernel<false, false>);
-    hipLaunchKernelGGL(kern, grid, dim3(256), LDS, st, a, w, ws, direct, M, Nrows, K, p.n_tiles, p.kt_per_split, p.rows);
+    if (p.rb == 2) {
+        auto kern = mode == 2 ? gemm_skinny_kernel<true, true, 2> : gemm_skinny_kernel<false, true, 2>;
+        hipLaunchKernelGGL(kern, grid, dim3(256), SkCfg<2>::kLds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles,
+                           p.kt_per_split, p.rows);
+    } else {
+        auto kern = mode == 2 ? gemm_skinny_kernel<true, false, 1> : gemm_skinny_kernel<false, false, 1>;
+        hipLaunchKernelGGL(kern, grid, dim3(256), SkCfg<1>::kLds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles,
+                           p.kt_per_split, p.rows);
+    }
     if (direct) return 0;
     return p.ksplit;
 }
