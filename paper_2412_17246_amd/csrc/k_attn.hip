@@ -622,13 +622,14 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
         num *= keep;
         den *= keep;
         M = Mb;
+        // no branches here: behind one the compiler moves each load next to its use and the batch turns
+        // into sixteen round trips.  A chunk past the end gets weight zero and adds exactly nothing.
 #pragma unroll
-        for (int u = 0; u < NB; ++u)
-            if (c0 + u < nch) {
-                const float w = exp2f(mv[u] - M);
-                num = fmaf(ov[u], w, num);
-                den = fmaf(lv[u], w, den);
-            }
+        for (int u = 0; u < NB; ++u) {
+            const float w = (c0 + u < nch) ? exp2f(mv[u] - M) : 0.f;
+            num = fmaf(ov[u], w, num);
+            den = fmaf(lv[u], w, den);
+        }
     }
     act_t r;
     from_f32(r, num / den);
