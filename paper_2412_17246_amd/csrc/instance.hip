@@ -96,7 +96,7 @@ void ws_layout(const bz_config* c, WsLayout* w) {
             t = gemm_workspace_bytes(1, M, c->hidden, c->ffn); if (t > g) g = t;
         };
         need(c->max_tokens < 64 ? c->max_tokens : 64);
-        for (int M = 512; M < c->max_tokens + 256; M += 256) need(M < c->max_tokens ? M : c->max_tokens);
+        for (int M = 256; M < c->max_tokens + 256; M += 256) need(M < c->max_tokens ? M : c->max_tokens);
         w->gemm_ws_bytes = g;
         w->gemm_ws = take(g);
     }

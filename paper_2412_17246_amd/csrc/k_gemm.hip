@@ -482,8 +482,12 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
+                // a 32-token block wholly past the last row is never read back (a few hundred rows fill
+                // only part of a 256-row tile, and the partial tiles are most of the traffic then)
+                if (m0 + (wave_u / WN) * 128 + i * 32 < M) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) base[((j * 4 + i) * 16 + r) * 64 + lane] = acc[j][i][r];
+                    for (int r = 0; r < 16; ++r) base[((j * 4 + i) * 16 + r) * 64 + lane] = acc[j][i][r];
+                }
                 __builtin_amdgcn_sched_barrier(0);     // one block at a time: few registers besides the accumulators are free
             }
         return;
@@ -560,6 +564,7 @@ __global__ __launch_bounds__(256) void gemm_big_fixup(const float* __restrict__ 
     int fb = 0;
 #pragma unroll
     for (int jj = 0; jj < NJE; ++jj) fb = (jj == j) ? fbase[jj] : fb;
+    if (bt.m0 + wm * 128 + i * 32 >= M) return;          // block past the last row: nothing was stored for it
     const int m = bt.m0 + wm * 128 + i * 32 + lrow;
     const int n = bt.n0 + fb + 8 * g + 4 * lk;
     float acc[NV][4];
@@ -623,7 +628,11 @@ static BigPlan big_plan(int mode, int M, int N, int K) {
     p.splits = 1;
     p.ws_bytes = 0;
     const int full = tiles / kCUs * kCUs, rest = tiles - full;
-    if (full > 0 && rest > 0 && rest <= kMaxTail) {
+    // rest <= kMaxTail: the last round is at most half full (then two ranges of K per tile fit the chip).
+    // full == 0: fewer tiles than CUs altogether (a few hundred rows, or a narrow output); every tile is
+    // split, whatever their number, so that a mid-sized batch still puts the whole chip to streaming the
+    // weights.
+    if (rest > 0 && (rest <= kMaxTail || full == 0)) {
         int sp = kCUs / rest;
         if (sp > kMaxSplits) sp = kMaxSplits;
         if (sp > nk / kMinKt) sp = nk / kMinKt;
@@ -640,7 +649,7 @@ static BigPlan big_plan(int mode, int M, int N, int K) {
 }
 
 static bool big_ok(int M, int N, int K) {
-    return M > 256 && K % kBK == 0 && N % 4 == 0 && (uint64_t)M * K < 0x7fffffffull &&
+    return M > 64 && K % kBK == 0 && N % 4 == 0 && (uint64_t)M * K < 0x7fffffffull &&
            (uint64_t)2 * N * K < 0x7fffffffull;          // the large-tile kernel uses 32-bit byte offsets / 2
 }
 
@@ -673,8 +682,9 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
         p.tail = 0;
         p.splits = 1;
     }
-    hipLaunchKernelGGL(kern, dim3(p.n_dp), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K, p.tiles_m, p.tiles_n,
-                       p.n_dp, p.splits, ws);
+    if (p.n_dp > 0)
+        hipLaunchKernelGGL(kern, dim3(p.n_dp), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K, p.tiles_m, p.tiles_n,
+                           p.n_dp, p.splits, ws);
     if (p.tail > 0) {
         hipLaunchKernelGGL(kern_part, dim3(p.tail * p.splits), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K,
                            p.tiles_m, p.tiles_n, p.n_dp, p.splits, ws);
