@@ -47,7 +47,7 @@ PEAK_HBM_GBPS = 8000.0
 # The gate/up figure covers the three launches of that projection (whole tiles, split last-round tiles,
 # their fix-up); the decode-attention figure covers the split-KV kernel and the combine.
 MEASURED_TRAFFIC = {("7b", 32, 6768, "gemm_gateup"): 1.881e9 + 0.150e9 + 0.069e9 + 0.061e9 + 0.061e9,
-                    ("8b_gqa", 32, 64, "attn_decode"): 0.5665e9 + 0.0119e9}
+                    ("8b_gqa", 32, 64, "attn_decode"): 0.5671e9 + 0.0114e9}
 
 
 # ------------------------------------------------------------------------------- helpers
