@@ -85,8 +85,8 @@ void ws_layout(const bz_config* c, WsLayout* w) {
     const size_t chunks = (c->max_seq_len + kDecodeChunk - 1) / kDecodeChunk;
     w->partial = take((size_t)c->max_seqs * c->n_q_heads * chunks * decode_partial_stride(c->head_dim) * sizeof(float));
     {   // fp32 scratch of the GEMMs: the largest need of the four projections over every row count a
-        // call may bring (decode-sized: split-K partial sums; prefill-sized: partial tiles of the last,
-        // nearly empty round of tiles, which depends on the number of 256-row tiles only)
+        // call may bring (up to 256 rows: split-K partial sums, a plan per number of 64-row blocks and linear
+        // in the rows; beyond: partial tiles of split tiles, which depend on the number of 256-row tiles only)
         const int qd = c->n_q_heads * c->head_dim;
         size_t g = 0;
         auto need = [&](int M) {
@@ -95,7 +95,7 @@ void ws_layout(const bz_config* c, WsLayout* w) {
             t = gemm_workspace_bytes(2, M, c->ffn, c->hidden); if (t > g) g = t;
             t = gemm_workspace_bytes(1, M, c->hidden, c->ffn); if (t > g) g = t;
         };
-        need(c->max_tokens < 64 ? c->max_tokens : 64);
+        for (int M = 64; M <= 256; M += 64) need(M < c->max_tokens ? M : c->max_tokens);   // split-K kernel: per 64-row block
         for (int M = 256; M < c->max_tokens + 256; M += 256) need(M < c->max_tokens ? M : c->max_tokens);
         w->gemm_ws_bytes = g;
         w->gemm_ws = take(g);

@@ -695,7 +695,7 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Skinny kernel for decode-sized problems (M <= 64 rows): the weights are read from HBM exactly
+// Skinny kernel for decode-sized problems (M <= 128 rows, in blocks of 64): the weights are read from HBM exactly
 // once and that read is the whole cost, so the job is to keep every CU streaming.  Work is cut
 // into tiles of 64 * RB weight rows times KSPLIT slices of K (a function of the shape only); each
 // workgroup streams its weight slice and the matching activation slice through a ring of LDS
@@ -742,12 +742,21 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
                                                                            const bf16* __restrict__ W,
                                                                            float* __restrict__ partial,
                                                                            bf16* __restrict__ C, int M, int Nrows, int K,
-                                                                           int n_tiles, int kt_per_split, int rows) {
+                                                                           int n_tiles, int kt_per_split, int rows,
+                                                                           int m_blocks, int units) {
     constexpr int kStage = SkCfg<RB>::kStage, kStages = SkCfg<RB>::kStages;
     constexpr int LPS = 2 + 2 * RB;                   // loads per wave and stage
     constexpr int HALF = 32 * RB;                     // rows per wave along the features (GU: rows per factor)
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-    const int tile_n = blockIdx.x % n_tiles, split = blockIdx.x / n_tiles;
+    // A unit is one (tile, k-slice); with more than 64 activation rows it is worked on by m_blocks
+    // workgroups, 64 rows each.  Workgroups are handed to the eight XCDs in turn, so the workgroups of a
+    // unit are given ids 8 apart: same XCD, one right after the other, and the weights the first one
+    // pulls from HBM are found in that XCD's L2 by the others.
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int unit = (seq / m_blocks) * 8 + xcd;
+    if (unit >= units) return;
+    const int m0 = (seq % m_blocks) * 64;
+    const int tile_n = unit % n_tiles, split = unit / n_tiles;
     // `rows` <= 64 * RB weight rows of those the tile has room for are real (GU: rows / 2 of each factor);
     // the launcher picks it so that the grid fills the chip's workgroup slots evenly
     const int tr = GU ? rows >> 1 : rows;             // real rows per factor (GU) or per tile
@@ -769,7 +778,7 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int row = (wave * 2 + j) * 8 + (lane >> 3);
-        int xr = row;
+        int xr = m0 + row;
         if (xr > M - 1) xr = M - 1;
         x_src[j] = ((uint32_t)xr * (uint32_t)K + ((lane & 7) ^ swz(row)) * 8) * 2u;
     }
@@ -842,8 +851,8 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
         }
     }
 
-    // lane holds token wt*32 + lane%32 and, of block b of its wave's rows, features 8g + 4*(lane/32) + 0..3
-    const int m = wt * 32 + lrow;
+    // lane holds token m0 + wt*32 + lane%32 and, of block b of its wave's rows, features 8g + 4*(lane/32) + 0..3
+    const int m = m0 + wt * 32 + lrow;
     if (GU && C != nullptr) {
         // the up-factor waves hand their accumulators to the gate-factor waves (same lane, same
         // token half) through LDS, which is free once everyone has read the last stage
@@ -927,14 +936,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_epilogue(const float* __restr
 }
 
 struct SkinnyPlan {
-    int n_tiles, kt_per_split, ksplit, rows, rb;
+    int n_tiles, kt_per_split, ksplit, rows, rb, m_blocks;
     size_t ws_bytes;
 };
 
 template <int RB>
-static void skinny_plan_rb(SkinnyPlan& p, int Nrows, int nk) {
-    constexpr int kTile = 64 * RB, kSlots = SkCfg<RB>::kSlots;
+static void skinny_plan_rb(SkinnyPlan& p, int Nrows, int nk, int m_blocks) {
+    constexpr int kTile = 64 * RB;
+    const int kSlots = SkCfg<RB>::kSlots / m_blocks;   // units the chip holds at a time
     p.rb = RB;
+    p.m_blocks = m_blocks;
     p.n_tiles = (Nrows + kTile - 1) / kTile;
     int target = kSlots / p.n_tiles;              // aim at filling every workgroup slot once
     if (target < 1) target = 1;
@@ -963,13 +974,20 @@ static SkinnyPlan skinny_plan(int M, int N, int K, int mode) {
     SkinnyPlan p;
     const int Nrows = (mode == 2) ? 2 * N : N;
     const int nk = K / kBK;
-    if ((size_t)Nrows * K * sizeof(bf16) >= kSkStreamBytes) skinny_plan_rb<2>(p, Nrows, nk);
-    else skinny_plan_rb<1>(p, Nrows, nk);
+    const int m_blocks = (M + 63) / 64;
+    if ((size_t)Nrows * K * sizeof(bf16) >= kSkStreamBytes) skinny_plan_rb<2>(p, Nrows, nk, m_blocks);
+    else skinny_plan_rb<1>(p, Nrows, nk, m_blocks);
     p.ws_bytes = (size_t)p.ksplit * M * Nrows * sizeof(float);
     return p;
 }
 
-static bool skinny_ok(int M, int N, int K) { return M >= 1 && M <= 64 && K % kBK == 0 && N % 4 == 0; }
+// Up to two 64-row blocks the split-K kernel beats the large-tile kernel with every tile split (the four
+// projections of the 8B-GQA shape, 128 rows: 148 against 173 us); from three blocks on it loses (192 rows:
+// 215 against 203 us).
+#ifndef BZ_SK_MAX_M
+#define BZ_SK_MAX_M 128
+#endif
+static bool skinny_ok(int M, int N, int K) { return M >= 1 && M <= BZ_SK_MAX_M && K % kBK == 0 && N % 4 == 0; }
 
 size_t gemm_workspace_bytes(int mode, int M, int N, int K) {
     if (skinny_ok(M, N, K)) return skinny_plan(M, N, K, mode).ws_bytes;
@@ -1002,16 +1020,17 @@ static int launch_skinny_partial(int mode, const bf16* a, const bf16* w, bf16* c
                                   hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<2>::kLds);
         attr_set = true;
     }
-    const dim3 grid(p.n_tiles * p.ksplit);
+    const int units = p.n_tiles * p.ksplit;
+    const dim3 grid((units + 7) / 8 * 8 * p.m_blocks);
     bf16* direct = (mode == 2 && p.ksplit == 1) ? c : nullptr;
     if (p.rb == 2) {
         auto kern = mode == 2 ? gemm_skinny_kernel<true, true, 2> : gemm_skinny_kernel<false, true, 2>;
         hipLaunchKernelGGL(kern, grid, dim3(256), SkCfg<2>::kLds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles,
-                           p.kt_per_split, p.rows);
+                           p.kt_per_split, p.rows, p.m_blocks, units);
     } else {
         auto kern = mode == 2 ? gemm_skinny_kernel<true, false, 1> : gemm_skinny_kernel<false, false, 1>;
         hipLaunchKernelGGL(kern, grid, dim3(256), SkCfg<1>::kLds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles,
-                           p.kt_per_split, p.rows);
+                           p.kt_per_split, p.rows, p.m_blocks, units);
     }
     if (direct) return 0;
     return p.ksplit;
