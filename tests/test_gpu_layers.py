@@ -275,6 +275,18 @@ def test_long_caches(torch, fp32, shape):
         assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
 
 
+@pytest.mark.parametrize("shape", [MIX, G8], ids=lambda s: s.name)
+def test_mixed_batch_of_65_to_128_rows(torch, shape):
+    # between the decode-sized kernels' 64 rows and their limit of 128: the projections run as two 64-row
+    # blocks and still leave partial sums for the rotary/append and norm kernels to fold
+    seqs = [(40, 0), (1, 40), (33, 16), (1, 0), (19, 7), (1, 300), (1, 255), (9, 100)]
+    assert 64 < sum(n for n, _ in seqs) <= 128
+    got, want, q_start = _mixed_case(torch, shape, False, seqs)
+    for i in range(len(seqs)):
+        a, b = q_start[i], q_start[i + 1]
+        assert U.rel_err(got[a:b], want[a:b]) <= U.BF16_TOL, (i, seqs[i])
+
+
 def test_first_causal_token_returns_v_row_on_the_gpu(torch):
     """Wo = identity-like routing is not available with random weights, so check the attention
     output itself: with one visible key, softmax weight is exactly 1 and the output is the V row,

@@ -50,6 +50,10 @@ GEMM_SHAPES = [
     (4300, 4092, 1024),
     # decode-sized problems (M <= 64, K a multiple of 64): the split-K kernel when a workspace is given
     (64, 4096, 4096), (33, 688, 1024), (7, 260, 640), (48, 1024, 14336),
+    # 65..128 rows: the same kernel, two 64-row blocks per tile and k-slice (second block ragged)
+    (128, 1024, 4096), (97, 688, 1024),
+    # a few hundred rows, fewer tiles than CUs: every tile of the large-tile kernel split over K
+    (200, 4096, 2048), (600, 1376, 4096),
 ]
 
 
