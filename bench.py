@@ -107,7 +107,7 @@ def cpu_baseline_prefill(shape):
     wts = {k: W.f32_from_bf16_bits(v).astype(np.float64) for k, v in W.layer_weights_bits(shape, 0).items()}
     x = W.f32_from_bf16_bits(W.hidden_bits(shape, n, step=0)).astype(np.float64)
     reps, used = 0, 0.0
-    while reps < 1 or (used < 10.0 and reps < 8):
+    while reps < 1 or (used < 10.0 and reps < 64):
         t0 = time.perf_counter()
         O.run_layers(osh, {0: wts}, 0, 1, x, O.OracleBatch([0, n], [0], [0]), O.OracleKV())
         used += time.perf_counter() - t0
@@ -127,7 +127,7 @@ def cpu_baseline_decode(shape, lens):
     rng = np.random.default_rng(5)
     x = W.f32_from_bf16_bits(W.hidden_bits(shape, B, step=0)).astype(np.float64)
     reps, used = 0, 0.0
-    while reps < 1 or (used < 10.0 and reps < 4):
+    while reps < 1 or (used < 10.0 and reps < 16):
         kv = O.OracleKV()
         for i, n in enumerate(lens):
             kv.put(0, i, rng.standard_normal((int(n), shape.Hkv, shape.d)), rng.standard_normal((int(n), shape.Hkv, shape.d)))
