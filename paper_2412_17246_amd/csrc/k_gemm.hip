@@ -695,7 +695,7 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Skinny kernel for decode-sized problems (M <= 128 rows, in blocks of 64): the weights are read from HBM exactly
+// Skinny kernel for decode-sized problems (M <= 256 rows): the weights are read from HBM exactly
 // once and that read is the whole cost, so the job is to keep every CU streaming.  Work is cut
 // into tiles of 64 * RB weight rows times KSPLIT slices of K (a function of the shape only); each
 // workgroup streams its weight slice and the matching activation slice through a ring of LDS
@@ -712,12 +712,15 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 // 70B qkv 40.9 -> 37.1, o 36.1 -> 37.8, gate/up 185 -> 168, down 96.5 -> 78.5 us.  (Three stages and
 // two workgroups per CU win on some of these shapes and lose on others.)
 // ---------------------------------------------------------------------------------------------
-template <int RB> struct SkCfg {
-    static constexpr int kStage = (64 + 64 * RB) * kBK * (int)sizeof(bf16);   // activations 8 KiB, weights 8 KiB * RB
+// TB = 32-row blocks of activation rows per wave: a workgroup covers 64 * TB rows (64 when the batch
+// has no more; 128 beyond, so that 65..128 rows still read every weight once and 129..256 rows twice).
+template <int RB, int TB> struct SkCfg {
+    static constexpr int kXBytes = 64 * TB * kBK * (int)sizeof(bf16);         // activations of a stage: 8 KiB * TB
+    static constexpr int kStage = kXBytes + 64 * RB * kBK * (int)sizeof(bf16);  // + weights 8 KiB * RB
 #ifndef BZ_SK2_STAGES
 #define BZ_SK2_STAGES 5
 #endif
-    static constexpr int kStages = RB == 1 ? 4 : BZ_SK2_STAGES;
+    static constexpr int kStages = (RB == 1 && TB == 1) ? 4 : BZ_SK2_STAGES;
     static constexpr int kLds = kStage * kStages;
     static constexpr int kPerCu = kLds * 2 <= 160 * 1024 ? 2 : 1;
     static constexpr int kSlots = 256 * kPerCu;                               // workgroups the chip holds at a time
@@ -737,25 +740,27 @@ __device__ __forceinline__ constexpr int sk_wait(int n) { return ((n >> 4) << 14
 // features (rows N + n0..), so that with a single k-slice the workgroup holds both factors of
 // silu(gate) * up and writes the activation itself (C != nullptr) instead of partial sums.
 // NT: the weight loads carry the non-temporal cache policy.
-template <bool GU, bool NT, int RB>
-__global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(const bf16* __restrict__ X,
-                                                                           const bf16* __restrict__ W,
-                                                                           float* __restrict__ partial,
-                                                                           bf16* __restrict__ C, int M, int Nrows, int K,
-                                                                           int n_tiles, int kt_per_split, int rows,
-                                                                           int m_blocks, int units) {
-    constexpr int kStage = SkCfg<RB>::kStage, kStages = SkCfg<RB>::kStages;
-    constexpr int LPS = 2 + 2 * RB;                   // loads per wave and stage
+template <bool GU, bool NT, int RB, int TB>
+__global__ __launch_bounds__(256, (SkCfg<RB, TB>::kPerCu)) void gemm_skinny_kernel(const bf16* __restrict__ X,
+                                                                                   const bf16* __restrict__ W,
+                                                                                   float* __restrict__ partial,
+                                                                                   bf16* __restrict__ C, int M, int Nrows,
+                                                                                   int K, int n_tiles, int kt_per_split,
+                                                                                   int rows, int m_blocks, int units) {
+    using Cfg = SkCfg<RB, TB>;
+    constexpr int kStage = Cfg::kStage, kStages = Cfg::kStages, kXBytes = Cfg::kXBytes;
+    constexpr int LPS = 2 * TB + 2 * RB;              // loads per wave and stage
     constexpr int HALF = 32 * RB;                     // rows per wave along the features (GU: rows per factor)
+    constexpr int MT = 64 * TB;                       // activation rows per workgroup
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-    // A unit is one (tile, k-slice); with more than 64 activation rows it is worked on by m_blocks
-    // workgroups, 64 rows each.  Workgroups are handed to the eight XCDs in turn, so the workgroups of a
+    // A unit is one (tile, k-slice); with more activation rows than a workgroup covers it is worked on by
+    // m_blocks workgroups.  Workgroups are handed to the eight XCDs in turn, so the workgroups of a
     // unit are given ids 8 apart: same XCD, one right after the other, and the weights the first one
     // pulls from HBM are found in that XCD's L2 by the others.
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
     const int unit = (seq / m_blocks) * 8 + xcd;
     if (unit >= units) return;
-    const int m0 = (seq % m_blocks) * 64;
+    const int m0 = (seq % m_blocks) * MT;
     const int tile_n = unit % n_tiles, split = unit / n_tiles;
     // `rows` <= 64 * RB weight rows of those the tile has room for are real (GU: rows / 2 of each factor);
     // the launcher picks it so that the grid fills the chip's workgroup slots evenly
@@ -772,12 +777,12 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
     const int lrow = lane & 31, lk = lane >> 5;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-    // loader: 1 KiB chunks of 8 rows; chunks 0..7 of a stage hold the activation rows, the 8 * RB after
-    // them the weight rows; this wave fills chunks 2*wave, 2*wave+1 of the former and 2*RB of the latter
-    uint32_t x_src[2], w_src[2 * RB];
+    // loader: 1 KiB chunks of 8 rows; the first 8 * TB chunks of a stage hold the activation rows, the
+    // 8 * RB after them the weight rows; this wave fills 2 * TB of the former and 2 * RB of the latter
+    uint32_t x_src[2 * TB], w_src[2 * RB];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int row = (wave * 2 + j) * 8 + (lane >> 3);
+    for (int j = 0; j < 2 * TB; ++j) {
+        const int row = (wave * 2 * TB + j) * 8 + (lane >> 3);
         int xr = m0 + row;
         if (xr > M - 1) xr = M - 1;
         x_src[j] = ((uint32_t)xr * (uint32_t)K + ((lane & 7) ^ swz(row)) * 8) * 2u;
@@ -803,22 +808,24 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
         const char* wk = reinterpret_cast<const char*>(W + (size_t)kt * kBK);
         unsigned char* sb = smem_raw + stage * kStage;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-            __builtin_amdgcn_global_load_lds((gptr_t)(xk + x_src[j]), (lptr_t)(sb + (wave_u * 2 + j) * 1024), 16, 0, 0);
+        for (int j = 0; j < 2 * TB; ++j)
+            __builtin_amdgcn_global_load_lds((gptr_t)(xk + x_src[j]), (lptr_t)(sb + (wave_u * 2 * TB + j) * 1024), 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < 2 * RB; ++j)
-            __builtin_amdgcn_global_load_lds((gptr_t)(wk + w_src[j]), (lptr_t)(sb + 8192 + (wave_u * 2 * RB + j) * 1024), 16,
-                                             0, NT ? 2 : 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wk + w_src[j]), (lptr_t)(sb + kXBytes + (wave_u * 2 * RB + j) * 1024),
+                                             16, 0, NT ? 2 : 0);
     };
 
-    f32x16 acc[RB];
+    f32x16 acc[RB][TB];
 #pragma unroll
     for (int b = 0; b < RB; ++b)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][t][r] = 0.f;
     const int sw = swz(lrow);
-    const int x_off = (wt * 32 + lrow) * 128;
-    const int w_off = 8192 + (wf * HALF + lrow) * 128;
+    const int x_off = (wt * 32 * TB + lrow) * 128;
+    const int w_off = kXBytes + (wf * HALF + lrow) * 128;
 
     // prologue: up to kStages - 1 tiles in flight
 #pragma unroll
@@ -842,17 +849,20 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int ko = ((ks * 2 + lk) ^ sw) * 16;
-            const bf16x8 xf = *reinterpret_cast<const bf16x8*>(st + x_off + ko);
+            bf16x8 xf[TB];
+#pragma unroll
+            for (int t = 0; t < TB; ++t) xf[t] = *reinterpret_cast<const bf16x8*>(st + x_off + t * 32 * 128 + ko);
 #pragma unroll
             for (int b = 0; b < RB; ++b) {
                 const bf16x8 wfr = *reinterpret_cast<const bf16x8*>(st + w_off + b * 32 * 128 + ko);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr, xf, acc[b], 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < TB; ++t) acc[b][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr, xf[t], acc[b][t], 0, 0, 0);
             }
         }
     }
 
-    // lane holds token m0 + wt*32 + lane%32 and, of block b of its wave's rows, features 8g + 4*(lane/32) + 0..3
-    const int m = m0 + wt * 32 + lrow;
+    // lane holds, of token block t, token m0 + wt*32*TB + t*32 + lane%32 and, of block b of its wave's rows,
+    // features 8g + 4*(lane/32) + 0..3
     if (GU && C != nullptr) {
         // the up-factor waves hand their accumulators to the gate-factor waves (same lane, same
         // token half) through LDS, which is free once everyone has read the last stage
@@ -862,31 +872,42 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
 #pragma unroll
             for (int b = 0; b < RB; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) ex[((wt * RB + b) * 16 + r) * 64 + lane] = acc[b][r];
+                for (int t = 0; t < TB; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) ex[(((wt * RB + b) * TB + t) * 16 + r) * 64 + lane] = acc[b][t][r];
         }
         __syncthreads();
-        if (wf == 0 && m < M) {
+        if (wf == 0) {
 #pragma unroll
-            for (int b = 0; b < RB; ++b)
+            for (int t = 0; t < TB; ++t) {
+                const int m = m0 + wt * 32 * TB + t * 32 + lrow;
+                if (m >= M) continue;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int lf = b * 32 + 8 * g + 4 * lk;
-                    const int nn = n0 + lf;
-                    if (lf < tr && nn < Nh) {
-                        bf16x4 w4;
+                for (int b = 0; b < RB; ++b)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float o = acc[b][4 * g + e], u = ex[((wt * RB + b) * 16 + 4 * g + e) * 64 + lane];
-                            w4[e] = (bf16)(o / (1.0f + __expf(-o)) * u);
+                    for (int g = 0; g < 4; ++g) {
+                        const int lf = b * 32 + 8 * g + 4 * lk;
+                        const int nn = n0 + lf;
+                        if (lf < tr && nn < Nh) {
+                            bf16x4 w4;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float o = acc[b][t][4 * g + e];
+                                const float u = ex[(((wt * RB + b) * TB + t) * 16 + 4 * g + e) * 64 + lane];
+                                w4[e] = (bf16)(o / (1.0f + __expf(-o)) * u);
+                            }
+                            *reinterpret_cast<bf16x4*>(C + (size_t)m * Nh + nn) = w4;
                         }
-                        *reinterpret_cast<bf16x4*>(C + (size_t)m * Nh + nn) = w4;
                     }
-                }
+            }
         }
         return;
     }
-    if (m < M) {                                       // partial[split][m][n]
-        float* prow = partial + ((size_t)split * M + m) * Nrows;
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        const int m = m0 + wt * 32 * TB + t * 32 + lrow;
+        if (m >= M) continue;
+        float* prow = partial + ((size_t)split * M + m) * Nrows;       // partial[split][m][n]
 #pragma unroll
         for (int b = 0; b < RB; ++b)
 #pragma unroll
@@ -896,7 +917,7 @@ __global__ __launch_bounds__(256, SkCfg<RB>::kPerCu) void gemm_skinny_kernel(con
                 const int nn = GU ? wf * Nh + f : f;
                 if (lf < tr && f < (GU ? Nh : Nrows))
                     *reinterpret_cast<float4*>(prow + nn) =
-                        make_float4(acc[b][4 * g], acc[b][4 * g + 1], acc[b][4 * g + 2], acc[b][4 * g + 3]);
+                        make_float4(acc[b][t][4 * g], acc[b][t][4 * g + 1], acc[b][t][4 * g + 2], acc[b][t][4 * g + 3]);
             }
     }
 }
@@ -936,15 +957,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_epilogue(const float* __restr
 }
 
 struct SkinnyPlan {
-    int n_tiles, kt_per_split, ksplit, rows, rb, m_blocks;
+    int n_tiles, kt_per_split, ksplit, rows, rb, tb, m_blocks;
     size_t ws_bytes;
 };
 
-template <int RB>
+template <int RB, int TB>
 static void skinny_plan_rb(SkinnyPlan& p, int Nrows, int nk, int m_blocks) {
     constexpr int kTile = 64 * RB;
-    const int kSlots = SkCfg<RB>::kSlots / m_blocks;   // units the chip holds at a time
+    const int kSlots = SkCfg<RB, TB>::kSlots / m_blocks;   // units the chip holds at a time
     p.rb = RB;
+    p.tb = TB;
     p.m_blocks = m_blocks;
     p.n_tiles = (Nrows + kTile - 1) / kTile;
     int target = kSlots / p.n_tiles;              // aim at filling every workgroup slot once
@@ -974,18 +996,24 @@ static SkinnyPlan skinny_plan(int M, int N, int K, int mode) {
     SkinnyPlan p;
     const int Nrows = (mode == 2) ? 2 * N : N;
     const int nk = K / kBK;
-    const int m_blocks = (M + 63) / 64;
-    if ((size_t)Nrows * K * sizeof(bf16) >= kSkStreamBytes) skinny_plan_rb<2>(p, Nrows, nk, m_blocks);
-    else skinny_plan_rb<1>(p, Nrows, nk, m_blocks);
+    const bool stream = (size_t)Nrows * K * sizeof(bf16) >= kSkStreamBytes;
+    if (M <= 64) {
+        if (stream) skinny_plan_rb<2, 1>(p, Nrows, nk, 1);
+        else skinny_plan_rb<1, 1>(p, Nrows, nk, 1);
+    } else {
+        const int m_blocks = (M + 127) / 128;
+        if (stream) skinny_plan_rb<2, 2>(p, Nrows, nk, m_blocks);
+        else skinny_plan_rb<1, 2>(p, Nrows, nk, m_blocks);
+    }
     p.ws_bytes = (size_t)p.ksplit * M * Nrows * sizeof(float);
     return p;
 }
 
-// Up to two 64-row blocks the split-K kernel beats the large-tile kernel with every tile split (the four
-// projections of the 8B-GQA shape, 128 rows: 148 against 173 us); from three blocks on it loses (192 rows:
-// 215 against 203 us).
+// Beyond 64 rows a workgroup covers 128.  Against the large-tile kernel with every tile split (the four
+// projections of the 8B-GQA shape, us): 65 rows 118 / 167, 128 rows 130 / 182, 192 rows 207 / 204,
+// 256 rows 215 / 228; with three blocks (384 rows) it loses, 319 / 250.
 #ifndef BZ_SK_MAX_M
-#define BZ_SK_MAX_M 128
+#define BZ_SK_MAX_M 256
 #endif
 static bool skinny_ok(int M, int N, int K) { return M >= 1 && M <= BZ_SK_MAX_M && K % kBK == 0 && N % 4 == 0; }
 
@@ -1008,29 +1036,24 @@ static int launch_skinny_partial(int mode, const bf16* a, const bf16* w, bf16* c
                                  hipStream_t st) {
     const SkinnyPlan p = skinny_plan(M, N, K, mode);
     const int Nrows = (mode == 2) ? 2 * N : N;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<false, false, 1>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<1>::kLds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<true, false, 1>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<1>::kLds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<false, true, 2>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<2>::kLds);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<true, true, 2>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, SkCfg<2>::kLds);
-        attr_set = true;
-    }
     const int units = p.n_tiles * p.ksplit;
     const dim3 grid((units + 7) / 8 * 8 * p.m_blocks);
     bf16* direct = (mode == 2 && p.ksplit == 1) ? c : nullptr;
-    if (p.rb == 2) {
-        auto kern = mode == 2 ? gemm_skinny_kernel<true, true, 2> : gemm_skinny_kernel<false, true, 2>;
-        hipLaunchKernelGGL(kern, grid, dim3(256), SkCfg<2>::kLds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles,
-                           p.kt_per_split, p.rows, p.m_blocks, units);
+    auto go = [&](auto kern, int lds) {
+        // raising the LDS limit is a per-function setting; asking again is cheap and keeps this free of state
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles, p.kt_per_split, p.rows,
+                           p.m_blocks, units);
+    };
+    const bool gu = mode == 2;
+    if (p.rb == 2 && p.tb == 2) {
+        if (gu) go(gemm_skinny_kernel<true, true, 2, 2>, SkCfg<2, 2>::kLds); else go(gemm_skinny_kernel<false, true, 2, 2>, SkCfg<2, 2>::kLds);
+    } else if (p.rb == 2) {
+        if (gu) go(gemm_skinny_kernel<true, true, 2, 1>, SkCfg<2, 1>::kLds); else go(gemm_skinny_kernel<false, true, 2, 1>, SkCfg<2, 1>::kLds);
+    } else if (p.tb == 2) {
+        if (gu) go(gemm_skinny_kernel<true, false, 1, 2>, SkCfg<1, 2>::kLds); else go(gemm_skinny_kernel<false, false, 1, 2>, SkCfg<1, 2>::kLds);
     } else {
-        auto kern = mode == 2 ? gemm_skinny_kernel<true, false, 1> : gemm_skinny_kernel<false, false, 1>;
-        hipLaunchKernelGGL(kern, grid, dim3(256), SkCfg<1>::kLds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles,
-                           p.kt_per_split, p.rows, p.m_blocks, units);
+        if (gu) go(gemm_skinny_kernel<true, false, 1, 1>, SkCfg<1, 1>::kLds); else go(gemm_skinny_kernel<false, false, 1, 1>, SkCfg<1, 1>::kLds);
     }
     if (direct) return 0;
     return p.ksplit;
