@@ -275,12 +275,16 @@ def test_long_caches(torch, fp32, shape):
         assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
 
 
+@pytest.mark.parametrize("extra", [0, 90], ids=["105rows", "195rows"])
 @pytest.mark.parametrize("shape", [MIX, G8], ids=lambda s: s.name)
-def test_mixed_batch_of_65_to_128_rows(torch, shape):
-    # between the decode-sized kernels' 64 rows and their limit of 128: the projections run as two 64-row
-    # blocks and still leave partial sums for the rotary/append and norm kernels to fold
+def test_mixed_batch_of_65_to_256_rows(torch, shape, extra):
+    # beyond the 64 rows of a decode-sized batch the split-K projections work in blocks of 128 rows (one block
+    # up to 128 rows, two up to 256) and still leave partial sums for the rotary/append and norm kernels to fold
     seqs = [(40, 0), (1, 40), (33, 16), (1, 0), (19, 7), (1, 300), (1, 255), (9, 100)]
-    assert 64 < sum(n for n, _ in seqs) <= 128
+    if extra:
+        seqs.append((extra, 3))
+    rows = sum(n for n, _ in seqs)
+    assert (64 < rows <= 128) if not extra else (128 < rows <= 256)
     got, want, q_start = _mixed_case(torch, shape, False, seqs)
     for i in range(len(seqs)):
         a, b = q_start[i], q_start[i + 1]
