@@ -328,9 +328,9 @@ int bz_op_rmsnorm(const void* x, const void* gain, void* y, int T, int H, float 
  * mode 1: c[M,N] = r[M,N] + a * w^T          (r may alias c)
  * mode 2: w is [2N,K] (gate rows then up rows): c[M,N] = silu(a*wg^T) .* (a*wu^T)
  * `workspace`: device scratch of at least bz_op_gemm_workspace_bytes(mode, M, N, K) bytes, 16-byte
- * aligned.  Decode-sized problems (M <= 64) split K over workgroups and keep partial sums there;
- * prefill-sized problems whose tile count leaves a small last round split those tiles over K and
- * keep partial tiles there.  With NULL or too small a workspace a schedule that needs none is used
+ * aligned.  Problems of up to 256 rows split K over workgroups and keep partial sums there;
+ * larger ones whose tile count is below the number of compute units, or leaves a small last
+ * round, split those tiles over K and keep partial tiles there.  With NULL or too small a workspace a schedule that needs none is used
  * (same result up to fp32 summation order); bz_run_layers always provides one. */
 size_t bz_op_gemm_workspace_bytes(int mode, int M, int N, int K);
 int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K, void* workspace,
