@@ -1028,6 +1028,24 @@ static bool skinny_applies(int mode, int M, int N, int K, const float* ws, size_
            (uint64_t)2 * N * K < 0x7fffffffull;
 }
 
+struct SkinnyArgs {
+    const bf16* a; const bf16* w; float* ws; bf16* direct;
+    int M, Nrows, K, n_tiles, kt_per_split, rows, m_blocks, units;
+};
+
+template <bool GU, bool NT, int RB, int TB>
+static void skinny_go(dim3 grid, hipStream_t st, const SkinnyArgs& g) {
+    constexpr int lds = SkCfg<RB, TB>::kLds;
+    static bool raised = false;          // per instantiation: the LDS limit is a per-function setting
+    if (!raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<GU, NT, RB, TB>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        raised = true;
+    }
+    hipLaunchKernelGGL((gemm_skinny_kernel<GU, NT, RB, TB>), grid, dim3(256), lds, st, g.a, g.w, g.ws, g.direct, g.M,
+                       g.Nrows, g.K, g.n_tiles, g.kt_per_split, g.rows, g.m_blocks, g.units);
+}
+
 // Split-K partial sums only: partial[ksplit][M][Nrows] (Nrows = 2N in SwiGLU mode).  The caller
 // folds the slices in slice order, either with gemm_skinny_epilogue or fused into the next kernel.
 // `c` (gate/up mode only): where the activation goes when one k-slice covers K; then the return value is 0
@@ -1039,21 +1057,16 @@ static int launch_skinny_partial(int mode, const bf16* a, const bf16* w, bf16* c
     const int units = p.n_tiles * p.ksplit;
     const dim3 grid((units + 7) / 8 * 8 * p.m_blocks);
     bf16* direct = (mode == 2 && p.ksplit == 1) ? c : nullptr;
-    auto go = [&](auto kern, int lds) {
-        // raising the LDS limit is a per-function setting; asking again is cheap and keeps this free of state
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a, w, ws, direct, M, Nrows, K, p.n_tiles, p.kt_per_split, p.rows,
-                           p.m_blocks, units);
-    };
+    const SkinnyArgs args{a, w, ws, direct, M, Nrows, K, p.n_tiles, p.kt_per_split, p.rows, p.m_blocks, units};
     const bool gu = mode == 2;
     if (p.rb == 2 && p.tb == 2) {
-        if (gu) go(gemm_skinny_kernel<true, true, 2, 2>, SkCfg<2, 2>::kLds); else go(gemm_skinny_kernel<false, true, 2, 2>, SkCfg<2, 2>::kLds);
+        if (gu) skinny_go<true, true, 2, 2>(grid, st, args); else skinny_go<false, true, 2, 2>(grid, st, args);
     } else if (p.rb == 2) {
-        if (gu) go(gemm_skinny_kernel<true, true, 2, 1>, SkCfg<2, 1>::kLds); else go(gemm_skinny_kernel<false, true, 2, 1>, SkCfg<2, 1>::kLds);
+        if (gu) skinny_go<true, true, 2, 1>(grid, st, args); else skinny_go<false, true, 2, 1>(grid, st, args);
     } else if (p.tb == 2) {
-        if (gu) go(gemm_skinny_kernel<true, false, 1, 2>, SkCfg<1, 2>::kLds); else go(gemm_skinny_kernel<false, false, 1, 2>, SkCfg<1, 2>::kLds);
+        if (gu) skinny_go<true, false, 1, 2>(grid, st, args); else skinny_go<false, false, 1, 2>(grid, st, args);
     } else {
-        if (gu) go(gemm_skinny_kernel<true, false, 1, 1>, SkCfg<1, 1>::kLds); else go(gemm_skinny_kernel<false, false, 1, 1>, SkCfg<1, 1>::kLds);
+        if (gu) skinny_go<true, false, 1, 1>(grid, st, args); else skinny_go<false, false, 1, 1>(grid, st, args);
     }
     if (direct) return 0;
     return p.ksplit;
