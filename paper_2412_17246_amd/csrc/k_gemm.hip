@@ -203,9 +203,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(const bf16*
 // instruction writes 1 KiB of LDS in lane order, i.e. 8 rows of 128 bytes; bank conflicts are
 // avoided by permuting WHICH 16-byte piece of its row each lane fetches (an XOR swizzle applied on
 // the global side) and reading operands with the same permutation.  The weight tile feeds the
-// MFMA's row operand and the activation tile its column operand, so a lane ends up with 4
-// consecutive output features of one token: 8-byte stores, and gate/up of the same feature in
-// the same lane for the SwiGLU epilogue.
+// MFMA's row operand and the activation tile its column operand, so a lane ends up with runs of
+// consecutive output features of one token (8 with the row order described at big_row_feature:
+// 16-byte stores), and gate/up of the same feature in the same lane for the SwiGLU epilogue.
 //
 // LDS is a ring of five 32 KiB slots, each holding one operand's 256 rows of one k-tile: the tile
 // being multiplied, the next one, and the activation half of the one after.  What decides the
@@ -231,6 +231,22 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // SIMD, 128x64 per wave).
 // logical tile id -> tile coordinates: groups of 4 tile rows, walked column by column, so that the
 // tiles running together on an XCD share operand rows in its L2
+// Which feature sits where.  A 32x32x16 MFMA leaves lane half h of the output with rows 8g + 4h + 0..3 of
+// the row operand (register group g = registers 4g..4g+3).  The weight rows of a 32-feature block are
+// therefore laid into LDS in a permuted order - operand row 8g + 4h + e holds feature
+// 16*(g/2) + 8h + 4*(g%2) + e - so that a lane's registers 8p..8p+7 are the 8 consecutive features
+// 16p + 8h + 0..7 of one token: 16-byte output stores, 32 contiguous bytes per token and instruction.  (In
+// operand-row order a lane would own 4 consecutive features; the L2 then takes the output as twice as many
+// partial-line writes, which is what bounds the epilogue.)  The permutation costs nothing: it only changes
+// which global row a loader lane fetches.
+__device__ __forceinline__ int big_row_feature(int rho) {            // operand row inside a block -> feature inside it
+    const int g = rho >> 3, h = (rho >> 2) & 1, e = rho & 3;
+    return 16 * (g >> 1) + 8 * h + 4 * (g & 1) + e;
+}
+__device__ __forceinline__ int big_group_feature(int g, int h) {     // first feature of register group g, lane half h
+    return 16 * (g >> 1) + 8 * h + 4 * (g & 1);
+}
+
 struct BigTile { int m0, n0; };
 template <int MODE>
 __device__ __forceinline__ BigTile big_tile_of(int pid, int tiles_m, int tiles_n) {
@@ -253,12 +269,32 @@ __device__ __forceinline__ void big_store_block(Get get, int m, int n0, const in
                                                 const bf16* R, bf16* C, int M, int N) {
     if (m >= M) return;
     bf16* crow = C + (size_t)m * N;
+    if ((N & 7) == 0 && MODE != 1) {                 // rows 16-byte aligned: 8 features (registers 8p..8p+7) per store
+        constexpr int NJE = (MODE == 2) ? NJ / 2 : NJ;
+#pragma unroll
+        for (int j = 0; j < NJE; ++j)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int n = n0 + fbase[j] + 16 * p + 8 * lk;
+                if (n < N) {
+                    bf16x8 o;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float v = get(j, 8 * p + e);
+                        if (MODE == 2) o[e] = (bf16)(v / (1.0f + __expf(-v)) * get(j + NJ / 2, 8 * p + e));
+                        else o[e] = (bf16)v;
+                    }
+                    *reinterpret_cast<bf16x8*>(crow + n) = o;
+                }
+            }
+        return;
+    }
     if (MODE == 2) {
 #pragma unroll
         for (int j = 0; j < NJ / 2; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n0 + fbase[j] + 8 * g + 4 * lk;
+                const int n = n0 + fbase[j] + big_group_feature(g, lk);
                 if (n < N) {
                     bf16x4 o;
 #pragma unroll
@@ -274,7 +310,7 @@ __device__ __forceinline__ void big_store_block(Get get, int m, int n0, const in
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n0 + fbase[j] + 8 * g + 4 * lk;
+                const int n = n0 + fbase[j] + big_group_feature(g, lk);
                 if (n < N) {
                     bf16x4 o;
                     if (MODE == 1) {
@@ -351,14 +387,15 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         int ar = m0 + row;
         if (ar > M - 1) ar = M - 1;
         a_off[j] = ((uint32_t)ar * (uint32_t)K + c * 8) * 2u;
+        const int frow = (row & ~31) | big_row_feature(row & 31);     // the feature this LDS row holds
         int br;
         if (MODE == 2) {
-            const bool up = row >= 128;
-            int f = n0 + (up ? row - 128 : row);
+            const bool up = frow >= 128;
+            int f = n0 + (up ? frow - 128 : frow);
             if (f > N - 1) f = N - 1;
             br = up ? N + f : f;
         } else {
-            br = n0 + row;
+            br = n0 + frow;
             if (br > N - 1) br = N - 1;
         }
         b_off[j] = ((uint32_t)br * (uint32_t)K + c * 8) * 2u;
@@ -492,12 +529,12 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
             }
         return;
     }
-    if (MODE == 1) {
-        // R may be C itself (the residual stream is updated in place), so written as load-then-store per
-        // element the compiler has to keep every load behind the store before it.  A lane reads exactly
-        // the addresses it writes: fetch a whole token block's residual values first, and the next
-        // block's before this block's stores go out.
-        bf16x4 rv[2][NJ * 4];
+    if (MODE == 1 && (N & 7) == 0) {
+        // R may be C itself (the residual stream is updated in place); a lane reads exactly the addresses it
+        // writes, so a token block's residual values are fetched together, and the next block's before this
+        // block's stores go out (written as load-then-store the loads would queue behind the stores).
+        // 16-byte form: registers 8p..8p+7 of feature block j are features 16p + 8*lk + 0..7.
+        bf16x8 rv[2][NJ * 2];
         auto load_r = [&](int i, int buf) {
             int m = m0 + wm * 128 + i * 32 + lrow;
             if (m > M - 1) m = M - 1;                   // rows and features past the end: a valid address, value unused
@@ -505,10 +542,10 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    int n = n0 + fbase[j] + 8 * g + 4 * lk;
-                    if (n > N - 4) n = N - 4;
-                    rv[buf][j * 4 + g] = *reinterpret_cast<const bf16x4*>(rrow + n);
+                for (int p = 0; p < 2; ++p) {
+                    int n = n0 + fbase[j] + 16 * p + 8 * lk;
+                    if (n > N - 8) n = N - 8;
+                    rv[buf][j * 2 + p] = *reinterpret_cast<const bf16x8*>(rrow + n);
                 }
         };
         load_r(0, 0);
@@ -522,13 +559,13 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = n0 + fbase[j] + 8 * g + 4 * lk;
+                    for (int p = 0; p < 2; ++p) {
+                        const int n = n0 + fbase[j] + 16 * p + 8 * lk;
                         if (n < N) {
-                            bf16x4 o;
+                            bf16x8 o;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[j][i][4 * g + e] + (float)rv[i & 1][j * 4 + g][e]);
-                            *reinterpret_cast<bf16x4*>(crow + n) = o;
+                            for (int e = 0; e < 8; ++e) o[e] = (bf16)(acc[j][i][8 * p + e] + (float)rv[i & 1][j * 2 + p][e]);
+                            *reinterpret_cast<bf16x8*>(crow + n) = o;
                         }
                     }
             }
@@ -536,6 +573,7 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         }
         return;
     }
+    // 8-byte form (N not a multiple of 8; a residual is then read element group by element group)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         big_store_block<MODE, NJ>([&](int j, int x) { return acc[j][i][x]; }, m0 + wm * 128 + i * 32 + lrow, n0, fbase,
@@ -566,7 +604,7 @@ __global__ __launch_bounds__(256) void gemm_big_fixup(const float* __restrict__ 
     for (int jj = 0; jj < NJE; ++jj) fb = (jj == j) ? fbase[jj] : fb;
     if (bt.m0 + wm * 128 + i * 32 >= M) return;          // block past the last row: nothing was stored for it
     const int m = bt.m0 + wm * 128 + i * 32 + lrow;
-    const int n = bt.n0 + fb + 8 * g + 4 * lk;
+    const int n = bt.n0 + fb + big_group_feature(g, lk);
     float acc[NV][4];
 #pragma unroll
     for (int v = 0; v < NV; ++v)
