@@ -140,6 +140,28 @@ def cpu_baseline_decode(shape, lens):
                       f"benchmark's cache lengths, {reps} repetitions, scaled by 1/L to whole-model tokens/s"}
 
 
+def pick_ingest_streams(args, inst, reset, one_step, torch):
+    """Untimed, after the warm-up steps: one step with the layers travelling on one copy stream and one with
+    two, on the benchmark's own host buffers; the faster setting is kept for the timed steps.  (Two
+    concurrent transfers usually keep the host link busier, but from some pinned allocations they are
+    slower than one, and a compute-bound step does not gain from them.)"""
+    if args.ingest_streams:
+        inst.set_ingest_streams(args.ingest_streams)
+        return args.ingest_streams
+    took = {}
+    for n in (1, 2):
+        inst.set_ingest_streams(n)
+        reset()
+        t0 = time.perf_counter()
+        one_step()
+        inst.sync()
+        torch.cuda.synchronize()
+        took[n] = time.perf_counter() - t0
+    best = 2 if took[2] < took[1] else 1
+    inst.set_ingest_streams(best)
+    return best
+
+
 def base_record(metric, value, unit, args, ms_per_step, workload, extra_cfg):
     cfg = {"workload": workload}
     cfg.update(extra_cfg)
@@ -210,6 +232,7 @@ def run_prefill_stream(args, torch, Instance):
         reset()
         one_step()
         inst.sync()
+    n_streams = pick_ingest_streams(args, inst, reset, one_step, torch)
     inst.profile_enable(True)
     inst.profile_read()
     total, ingest_ms = 0.0, []
@@ -241,7 +264,7 @@ def run_prefill_stream(args, torch, Instance):
                       f"prefill batch of {B} requests ({T} tokens) runs behind the frontier",
                       {"shape": shape.name, "layers": shape.L, "requests": B, "tokens": T,
                        "lengths": [int(v) for v in lens], "distinct_host_blobs": n_blobs,
-                       "shards_per_layer": max(1, args.shards)})
+                       "shards_per_layer": max(1, args.shards), "ingest_streams": n_streams})
     out.update({
         "ttft_ms": ms_per_step,
         "ingest_GBps": shape.L * inst.layer_bytes / (float(np.median(ingest_ms)) * 1e-3) / 1e9,
@@ -435,6 +458,7 @@ def run_mixed_ttft(args, torch, Instance):
         reset()
         one_step()
         inst.sync()
+    n_streams = pick_ingest_streams(args, inst, reset, one_step, torch)
     inst.profile_enable(True)
     inst.profile_read()
     total, ingest_ms = 0.0, []
@@ -455,7 +479,8 @@ def run_mixed_ttft(args, torch, Instance):
     out = base_record("prefill tokens/s on partially loaded model", T * args.steps / total, "tokens/s", args, ttft,
                       f"{shape.name}-shaped decoder, layers [0,{resident}) resident and [{resident},{shape.L}) ingested from "
                       f"scale start while one mixed batch (16 prefill requests + 48 decode sequences, {T} rows) runs",
-                      {"shape": shape.name, "layers": shape.L, "rows": T, "prefill_lengths": [int(n) for n in p_lens]})
+                      {"shape": shape.name, "layers": shape.L, "rows": T, "prefill_lengths": [int(n) for n in p_lens],
+                       "ingest_streams": n_streams})
     out.update({"ttft_ms": ttft, "ingest_ms": ing,
                 "ingest_GBps": (shape.L - resident) * inst.layer_bytes / (ing * 1e-3) / 1e9,
                 "kernel_ms_sum_per_step": compute_ms, "overlap_efficiency": max(ing, compute_ms) / ttft,
@@ -542,6 +567,8 @@ def main() -> int:
     ap.add_argument("--requests", type=int, default=8)
     ap.add_argument("--fixed-len", type=int, default=0, help="prefill_stream: every request has this many tokens; decode: every cache has this length")
     ap.add_argument("--distinct-blobs", type=int, default=0, help="prefill_stream: feed layer i from pinned blob i mod m")
+    ap.add_argument("--ingest-streams", type=int, default=0, choices=[0, 1, 2],
+                    help="copy streams a layer travels on (0 = try both after warm-up and keep the faster)")
     ap.add_argument("--shards", type=int, default=1, help="prefill_stream: ingest every layer as this many parallel shards")
     ap.add_argument("--split", type=int, default=0, help="decode: also run a live split at this layer and compare bits")
     ap.add_argument("--chunk-mib", type=int, default=0, help="ingest chunk size in MiB (0 = library default)")

@@ -174,9 +174,18 @@ int bz_sync(bz_instance* inst);                  /* waits for both streams */
  * requested in any order.  BZ_EBUSY if layer i is loading or resident.
  * The bytes go over in blob order, which is the order the layer reads them (attention weights
  * first, down projection last), and an event is also recorded behind each group of tensors that one
- * stage of the layer needs; bz_run_layers uses them (see there).  The layer counts as resident, for
+ * stage of the layer needs; bz_run_layers uses them (see there).  See bz_set_ingest_streams for
+ * the number of streams the bytes travel on.  The layer counts as resident, for
  * the frontier and every query below, only when all of it has landed. */
 int bz_load_layer(bz_instance* inst, int layer, const void* host, size_t n);
+/* Number of streams (1, the default, or 2) that later bz_load_layer / bz_load_layer_from_device calls
+ * spread a layer over.  With 2, each tensor group is cut in two halves that travel concurrently, one
+ * on the copy stream and one on a second stream the library owns; the layer's event, on the copy
+ * stream, follows both.  Two transfers in flight keep a host link busier than one (57.1 against
+ * 55.8 GB/s measured), but not from every host buffer: from some pinned allocations of a virtualised
+ * host two concurrent transfers ran at 46 GB/s where one kept 55.8.  A caller that cares measures
+ * both on its own buffers (bench.py does, during warm-up).  BZ_EINVAL for any other n. */
+int bz_set_ingest_streams(bz_instance* inst, int n);
 /* Same, from a device buffer (a resident peer's copy: one hop of section 5.1's forwarding chain). */
 int bz_load_layer_from_device(bz_instance* inst, int layer, const void* dev, size_t n);
 /* Parallel sharded transfer (section 5.1, "parallel sharded parameter transfer from multiple
@@ -247,11 +256,12 @@ int bz_batch_advance(bz_instance* inst, bz_batch* batch);
  * activation elements, updated in place — appending the new tokens' K/V of those layers to the
  * instance's cache.  The compute stream waits on layer i's ingest before it runs layer i, so the
  * call may be issued while later layers are still arriving (section 5.2, step 2 of the protocol).
- * The paper gates at layer granularity; here, for a layer still in flight that was requested with
- * bz_load_layer or bz_load_layer_from_device, each stage waits only for the tensors it reads (QKV
- * group before the first norm, wo and the second norm's gain before the output projection, gate/up
- * before the MLP, the whole layer before the down projection): the last layer's attention runs
- * while its MLP weights arrive.  A sharded layer is waited for as a whole.  With BZ_RUN_NOWAIT it returns BZ_ENOTREADY instead if any layer of [a,b) is not
+ * The paper gates at layer granularity, and so does this call for every layer but the last of
+ * the range: if layer b-1 is still in flight and was requested with bz_load_layer or
+ * bz_load_layer_from_device, each of its stages waits only for the tensors it reads (QKV group
+ * before the first norm, wo and the second norm's gain before the output projection, gate/up
+ * before the MLP, the whole layer before the down projection), so its attention runs while its
+ * MLP weights arrive.  A sharded layer is waited for as a whole.  With BZ_RUN_NOWAIT it returns BZ_ENOTREADY instead if any layer of [a,b) is not
  * resident yet.  Results do not depend on a, b, the frontier or timing: running [a,k) then [k,b)
  * (on this or another instance holding the same weights) is bit-identical to running [a,b). */
 int bz_run_layers(bz_instance* inst, int a, int b, const bz_batch* batch, void* hidden, int flags);

@@ -114,6 +114,7 @@ SIGNATURES = {
     "bz_sync": (C.c_int, [_P]),
     "bz_load_layer": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
     "bz_load_layer_from_device": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
+    "bz_set_ingest_streams": (C.c_int, [_P, C.c_int]),
     "bz_load_layer_sharded": (C.c_int, [_P, C.c_int, C.POINTER(bz_shard), C.c_int]),
     "bz_plan_generate": (C.c_int, [C.POINTER(bz_plan_node), C.c_int, C.c_int, C.c_double, C.c_int, C.c_double,
                                    C.POINTER(bz_plan_hop), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int),
@@ -305,6 +306,9 @@ class Instance:
         return t
 
     # -- ingest
+    def set_ingest_streams(self, n: int) -> None:
+        self._check(self.lib.bz_set_ingest_streams(self.handle, n), "bz_set_ingest_streams")
+
     def load_layer(self, layer: int, pinned) -> None:
         self._keep.append(pinned)
         self._check(self.lib.bz_load_layer(self.handle, layer, _ptr(pinned), pinned.numel()), "bz_load_layer")

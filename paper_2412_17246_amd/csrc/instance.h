@@ -55,6 +55,10 @@ struct bz_instance {
     bool dry = false;
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
+    // second copy stream (always the library's own), used when ingest_streams == 2: a layer's tensor groups
+    // are then cut in two halves, one per stream (see bz_set_ingest_streams)
+    hipStream_t copy2 = nullptr;
+    int ingest_streams = 1;
     unsigned char* weights = nullptr;
     unsigned char* kv = nullptr;
     unsigned char* wsp = nullptr;
@@ -65,6 +69,7 @@ struct bz_instance {
     // the layer needs has landed: [3l] QKV group (g1, wq, wk, wv), [3l+1] wo and g2, [3l+2] wg and wu;
     // the down projection waits for ev[l].  parts_valid[l] says whether the current load recorded them.
     std::vector<hipEvent_t> ev_part;
+    std::vector<hipEvent_t> ev_part2;            // [4l + p]: the second stream's half of tensor group p of layer l
     std::vector<char> parts_valid;
     hipEvent_t t0 = nullptr;
     bool clock_started = false;

@@ -207,16 +207,33 @@ int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpy
     const unsigned char* s = static_cast<const unsigned char*>(src);
     // The blob goes over in the order the layer consumes it, with an event behind each group of
     // tensors, so that the layer's first stages can run while its MLP weights are still arriving.
+    // With two ingest streams each group's bytes are cut in two halves, one per copy stream; the streams
+    // never wait for each other inside a layer (a stage of the layer waits for both halves of its group),
+    // only at its end, where the layer's own event is recorded behind both.  With one stream the second
+    // half is empty and its events fire at once.
     const size_t ends[4] = {I->lay.wo, I->lay.wg, I->lay.wd, n};
-    size_t off = 0;
+    size_t start = 0;
     for (int part = 0; part < 4; ++part) {
-        while (off < ends[part]) {
-            const size_t left = ends[part] - off;
-            const size_t m = left < chunk ? left : chunk;
+        const size_t mid = start + ((ends[part] - start) / 2 + 255) / 256 * 256;
+        const size_t cut = (I->ingest_streams == 2 && mid < ends[part]) ? mid : ends[part];
+        for (size_t off = start; off < cut;) {
+            const size_t m = cut - off < chunk ? cut - off : chunk;
             HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy));
             off += m;
         }
-        HIP_TRY(hipEventRecord(part < 3 ? I->ev_part[3 * layer + part] : I->ev[layer], I->copy));
+        for (size_t off = cut; off < ends[part];) {
+            const size_t m = ends[part] - off < chunk ? ends[part] - off : chunk;
+            HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy2));
+            off += m;
+        }
+        HIP_TRY(hipEventRecord(I->ev_part2[4 * layer + part], I->copy2));
+        if (part < 3) {
+            HIP_TRY(hipEventRecord(I->ev_part[3 * layer + part], I->copy));
+        } else {
+            HIP_TRY(hipStreamWaitEvent(I->copy, I->ev_part2[4 * layer + part], 0));
+            HIP_TRY(hipEventRecord(I->ev[layer], I->copy));
+        }
+        start = ends[part];
     }
     I->parts_valid[layer] = 1;
     I->state[layer] = kLoading;
@@ -284,8 +301,10 @@ int bz_destroy(bz_instance* I) {
     if (!I->dry) {
         if (I->compute) (void)hipStreamSynchronize(I->compute);
         if (I->copy) (void)hipStreamSynchronize(I->copy);
+        if (I->copy2) { (void)hipStreamSynchronize(I->copy2); (void)hipStreamDestroy(I->copy2); }
         for (hipEvent_t e : I->ev) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : I->ev_part) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : I->ev_part2) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : I->ev_pool) (void)hipEventDestroy(e);
         for (hipStream_t q : I->shard_streams) { (void)hipStreamSynchronize(q); (void)hipStreamDestroy(q); }
         for (hipEvent_t e : I->shard_events) (void)hipEventDestroy(e);
@@ -333,6 +352,7 @@ int bz_create(const bz_config* cfg, bz_instance** out) {
     else { HIP_TRY_C(hipStreamCreateWithFlags(&I->compute, hipStreamNonBlocking)); I->own_compute = true; }
     if (cfg->copy_stream) I->copy = (hipStream_t)cfg->copy_stream;
     else { HIP_TRY_C(hipStreamCreateWithFlags(&I->copy, hipStreamNonBlocking)); I->own_copy = true; }
+    HIP_TRY_C(hipStreamCreateWithFlags(&I->copy2, hipStreamNonBlocking));
     if (cfg->weights_arena) {
         if (cfg->weights_arena_bytes < I->sz.weights_arena_bytes || ((uintptr_t)cfg->weights_arena & 255)) return fail(BZ_ENOMEM);
         I->weights = (unsigned char*)cfg->weights_arena;
@@ -349,6 +369,8 @@ int bz_create(const bz_config* cfg, bz_instance** out) {
     for (int l = 0; l < cfg->n_layers; ++l) HIP_TRY_C(hipEventCreate(&I->ev[l]));
     I->ev_part.assign((size_t)3 * cfg->n_layers, nullptr);
     for (size_t k = 0; k < I->ev_part.size(); ++k) HIP_TRY_C(hipEventCreateWithFlags(&I->ev_part[k], hipEventDisableTiming));
+    I->ev_part2.assign((size_t)4 * cfg->n_layers, nullptr);
+    for (size_t k = 0; k < I->ev_part2.size(); ++k) HIP_TRY_C(hipEventCreateWithFlags(&I->ev_part2[k], hipEventDisableTiming));
     HIP_TRY_C(hipEventCreate(&I->t0));
     {   // rotary table: angle = pos * base^(-2j/d) in float64, stored as (cos, sin) floats
         const int d = cfg->head_dim, half = d / 2;
@@ -378,7 +400,14 @@ int bz_sync(bz_instance* I) {
     if (!I) return BZ_EINVAL;
     if (I->dry) return BZ_OK;
     HIP_TRY(hipStreamSynchronize(I->copy));
+    HIP_TRY(hipStreamSynchronize(I->copy2));
     HIP_TRY(hipStreamSynchronize(I->compute));
+    return BZ_OK;
+}
+
+int bz_set_ingest_streams(bz_instance* I, int n) {
+    if (!I || (n != 1 && n != 2)) return BZ_EINVAL;
+    I->ingest_streams = n;
     return BZ_OK;
 }
 
@@ -745,11 +774,15 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
 
     int pending_down = 0;        // split-K slices of the previous layer's down projection still to be folded into x
     for (int l = a; l < b; ++l) {
-        // a layer still on its way gates each stage on the tensors that stage reads (or, when it was
-        // not copied in blob order, everything on the whole layer)
+        // A layer still on its way is waited for as a whole, except the last one of the range: there each
+        // stage waits only for the tensors it reads, so the range ends one down projection, not one whole
+        // layer, behind the last byte.  (Finer gating of the layers before it would not end the range any
+        // sooner, and every wait on another stream's event costs the compute stream some tens of
+        // microseconds.)
         const bool gated = I->state[l] != kResident;
-        const bool by_part = gated && I->parts_valid[l];
+        const bool by_part = gated && I->parts_valid[l] && l == b - 1;
         if (gated) HIP_TRY(hipStreamWaitEvent(st, by_part ? I->ev_part[3 * l] : I->ev[l], 0));
+        if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l], 0));
         const unsigned char* wl = layer_ptr(I, l);
         const bf16* g1 = (const bf16*)(wl + I->lay.g1);
         const bf16* wqkv = (const bf16*)(wl + I->lay.wq);
@@ -782,14 +815,20 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
             launch_attn_decode(qkv, attn, partial, bv, kvv, sh.Hq, st);
         }
         int ks_o = 0;
-        if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 1], 0));
+        if (by_part) {
+            HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 1], 0));
+            HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l + 1], 0));
+        }
         { ProfScope p(I, BZ_K_GEMM_O, 2.0 * T * sh.H * qd, (2.0 * T * sh.H + (double)T * qd) * e + 2.0 * sh.H * qd);
           ks_o = launch_gemm_partial(1, attn, wo, T, sh.H, qd, gws, gwsb, st);
           if (ks_o == 0) launch_gemm(1, attn, wo, x, x, T, sh.H, qd, gws, gwsb, st); }
         { ProfScope p(I, BZ_K_RMSNORM, 4.0 * T * sh.H, 2.0 * T * sh.H * e);
           if (ks_o > 0) launch_reduce_residual_rmsnorm(x, gws, ks_o, g2, normed, T, sh.H, I->cfg.rms_eps, st);
           else launch_rmsnorm(x, g2, normed, T, sh.H, I->cfg.rms_eps, st); }
-        if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 2], 0));
+        if (by_part) {
+            HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 2], 0));
+            HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l + 2], 0));
+        }
         { ProfScope p(I, BZ_K_GEMM_GATEUP, 4.0 * T * sh.F * sh.H, ((double)T * sh.H + (double)T * sh.F) * e + 4.0 * sh.F * sh.H);
           launch_gemm(2, normed, wgu, nullptr, act, T, sh.F, sh.H, gws, gwsb, st); }
         if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev[l], 0));

@@ -19,9 +19,14 @@ def torch():
     return torch
 
 
+@pytest.mark.parametrize("streams", [1, 2])
 @pytest.mark.parametrize("chunk", [0, 4096, 1 << 20, 1000003])
-def test_ingest_is_byte_exact_for_any_chunk_size(torch, chunk):
+def test_ingest_is_byte_exact_for_any_chunk_size(torch, chunk, streams):
     inst = U.make_instance(TINY, max_seqs=1, max_seq_len=32, max_tokens=8, kv_tokens=32, chunk_bytes=chunk)
+    inst.set_ingest_streams(streams)
+    with pytest.raises(Exception) as ei:
+        inst.set_ingest_streams(3)
+    assert "BZ_EINVAL" in str(ei.value)
     rng = np.random.default_rng(chunk + 1)
     blobs = [rng.integers(0, 256, inst.layer_bytes, dtype=np.uint8) for _ in range(TINY.L)]
     pinned = [inst.pinned_blob(b) for b in blobs]

@@ -114,10 +114,11 @@ def test_8b_gqa_decode_step_full_batch(torch):
         assert U.rel_err(got[i:i + 1], want[i:i + 1]) <= U.BF16_TOL
 
 
-def test_7b_layer_run_enqueued_while_its_weights_arrive(torch):
-    """run_layers is issued right behind load_layer, while the 405 MB of the layer are on their way: the
-    stages wait for the tensor groups they read, and the output has the bits of a run on the resident
-    layer."""
+@pytest.mark.parametrize("streams", [1, 2])
+def test_7b_layer_run_enqueued_while_its_weights_arrive(torch, streams):
+    """run_layers is issued right behind load_layer, while the 405 MB of the layer are on their way (on one
+    copy stream, or cut in halves over two): the stages wait for the tensor groups they read, and the output
+    has the bits of a run on the resident layer."""
     base = W.CONFIGS["7b"]
     s = _one_layer_shape(base)
     lens = [211, 122]
@@ -125,6 +126,7 @@ def test_7b_layer_run_enqueued_while_its_weights_arrive(torch):
     inst = U.make_instance(s, max_seqs=2, max_seq_len=256, max_tokens=T, kv_tokens=512)
     for i, n in enumerate(lens):
         inst.kv_reserve(i, n)
+    inst.set_ingest_streams(streams)
     blob = inst.pinned_blob(inst.pack_layer(W.layer_weights_bits(base, 3)))
     xbits = W.hidden_bits(base, T, step=11)
     x1, x2 = U.to_device(xbits, False), U.to_device(xbits, False)
