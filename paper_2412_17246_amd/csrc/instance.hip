@@ -779,6 +779,10 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         // layer, behind the last byte.  (Finer gating of the layers before it would not end the range any
         // sooner, and every wait on another stream's event costs the compute stream some tens of
         // microseconds.)
+        if (I->state[l] == kLoading) {                   // may have landed since it was last looked at: then no wait at all
+            int rc = poll_layer(I, l);
+            if (rc) return rc;
+        }
         const bool gated = I->state[l] != kResident;
         const bool by_part = gated && I->parts_valid[l] && l == b - 1;
         if (gated) HIP_TRY(hipStreamWaitEvent(st, by_part ? I->ev_part[3 * l] : I->ev[l], 0));
