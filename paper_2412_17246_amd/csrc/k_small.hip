@@ -190,7 +190,17 @@ __global__ __launch_bounds__(256) void rope_append_kernel(act_t* __restrict__ qk
         return;
     }
     // a token's work is shared by `tsplit` workgroups (small batches: more CUs than tokens)
-    const int t = (blockIdx.x - n_vblocks) / tsplit, part = (blockIdx.x - n_vblocks) % tsplit;
+    int t = (blockIdx.x - n_vblocks) / tsplit;
+    const int part = (blockIdx.x - n_vblocks) % tsplit;
+    if (tsplit == 1) {
+        // One workgroup per token: workgroups go to the eight XCDs in turn, and a token's K row is 16-byte
+        // pieces that share their 128-byte lines with the 7 neighbouring positions.  Tokens are therefore
+        // dealt out in runs of 8 per XCD (n_vblocks is a multiple of 8, so blockIdx.x & 7 is the XCD), and
+        // the neighbours' pieces meet in one L2 instead of leaving eight partial lines in eight of them.
+        const int xcd = t & 7, seq = t >> 3;
+        t = ((seq >> 3) * 8 + xcd) * 8 + (seq & 7);
+        if (t >= bv.T) return;
+    }
     const int s = bv.token_seq[t];
     const int before = bv.kv_before[s];
     const int pos = before + (t - bv.q_start[s]);
@@ -281,7 +291,8 @@ void launch_rope_append(act_t* qkv, const float* rope_tab, const BatchView& bv, 
     if (bv.T <= 0) return;
     const int nvb = bv.n_prefill_items * 16;
     const int tsplit = bv.T < 256 ? 4 : 1;
-    hipLaunchKernelGGL(rope_append_kernel<false>, dim3(nvb + bv.T * tsplit), dim3(256), 0, st, qkv, nullptr, 0, rope_tab,
+    const int tblocks = tsplit == 1 ? (bv.T + 63) / 64 * 64 : bv.T * tsplit;      // runs of 8 tokens x 8 XCDs
+    hipLaunchKernelGGL(rope_append_kernel<false>, dim3(nvb + tblocks), dim3(256), 0, st, qkv, nullptr, 0, rope_tab,
                        bv, kv, Hq, nvb, tsplit);
 }
 
@@ -290,7 +301,8 @@ void launch_rope_append_reduce(act_t* qkv, const float* partial, int ksplit, con
     if (bv.T <= 0) return;
     const int nvb = bv.n_prefill_items * 16;
     const int tsplit = bv.T < 256 ? 4 : 1;
-    hipLaunchKernelGGL(rope_append_kernel<true>, dim3(nvb + bv.T * tsplit), dim3(256), 0, st, qkv, partial, ksplit,
+    const int tblocks = tsplit == 1 ? (bv.T + 63) / 64 * 64 : bv.T * tsplit;
+    hipLaunchKernelGGL(rope_append_kernel<true>, dim3(nvb + tblocks), dim3(256), 0, st, qkv, partial, ksplit,
                        rope_tab, bv, kv, Hq, nvb, tsplit);
 }
 
