@@ -430,3 +430,34 @@ def test_batch_advance_reports_when_its_chunk_list_is_full(torch):
     assert "BZ_ECAPACITY" in str(ei.value)
     inst.sync()
     inst.close()
+
+
+def test_decode_batch_of_300_sequences_with_advance(torch):
+    """More decode sequences than the 256 threads of the kernel that rebuilds the chunk list: the list is
+    built in several passes with a running offset."""
+    s, os_ = TINY, U.oracle_shape(TINY)
+    B, steps = 300, 2
+    lens = [(37 * i) % 290 + 1 for i in range(B)]            # 1..290: some sequences cross 256 while stepping
+    inst = U.make_instance(s, max_seqs=B, max_seq_len=320, max_tokens=B, kv_tokens=sum(lens) + 64 * B)
+    bits = {l: W.layer_weights_bits(s, l) for l in range(s.L)}
+    wts = {l: U.oracle_weights(bits[l]) for l in range(s.L)}
+    U.load_all_layers(inst, s)
+    okv = O.OracleKV()
+    for i, n in enumerate(lens):
+        inst.kv_reserve(i, n + steps)
+        for l in range(s.L):
+            kb, vb = W.kv_prefill_bits(s, l, i, n)
+            okv.put(l, i, U.f64(kb), U.f64(vb))
+            inst.kv_write(l, i, 0, n, kb, vb)
+    batch = inst.batch(list(range(B + 1)), list(range(B)), lens)
+    for step in range(steps):
+        xbits = W.hidden_bits(s, B, step=80 + step)
+        x = U.to_device(xbits, False)
+        torch.cuda.synchronize()
+        inst.run_layers(0, s.L, batch, x)
+        inst.batch_advance(batch)
+        inst.sync()
+        want = O.run_layers(os_, wts, 0, s.L, U.f64(xbits),
+                            O.OracleBatch(list(range(B + 1)), list(range(B)), [n + step for n in lens]), okv)
+        assert U.rel_err(U.from_device(x), want) <= U.BF16_TOL, step
+    inst.close()

@@ -51,7 +51,7 @@ GEMM_SHAPES = [
     # decode-sized problems (M <= 64, K a multiple of 64): the split-K kernel when a workspace is given
     (64, 4096, 4096), (33, 688, 1024), (7, 260, 640), (48, 1024, 14336),
     # 65..128 rows: the same kernel, two 64-row blocks per tile and k-slice (second block ragged)
-    (128, 1024, 4096), (97, 688, 1024),
+    (128, 1024, 4096), (97, 688, 1024), (100, 256, 4096), (250, 512, 2048),
     # a few hundred rows, fewer tiles than CUs: every tile of the large-tile kernel split over K
     (200, 4096, 2048), (600, 1376, 4096),
 ]
@@ -105,6 +105,21 @@ def test_gemm_residual_in_place_and_identity(torch):
     got = U.from_device(x)
     want = U.f64(__import__("workloads").bf16_bits_from_f32((xr + ar).astype(np.float32)))
     assert np.array_equal(got, want)            # one rounding of an exact sum
+
+
+@pytest.mark.parametrize("M,N,K", [(100, 512, 1024), (600, 1376, 4096), (4300, 4096, 1024)])
+def test_gemm_residual_in_place_with_split_schedules(torch, M, N, K):
+    # the residual aliased with the output, in the schedules that go through partial sums or partial tiles
+    from paper_2412_17246_amd import op_gemm, op_gemm_workspace_bytes
+    rng = np.random.default_rng([17, M, N, K])
+    a, ar = U.f64_to_device(rng.standard_normal((M, K)), False)
+    w, wr = U.f64_to_device(rng.standard_normal((N, K)) * (2.0 / np.sqrt(K)), False)
+    x, xr = U.f64_to_device(rng.standard_normal((M, N)), False)
+    nws = op_gemm_workspace_bytes(1, M, N, K)
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    op_gemm(1, a, w, x, x, M, N, K, workspace=ws)
+    assert U.rel_err(U.from_device(x), xr + O.linear(ar, wr)) <= U.BF16_TOL
 
 
 def test_gemm_is_deterministic(torch):
