@@ -54,7 +54,25 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* smem = reinterpret_cast<bf16*>(smem_raw);
 
-    const int item = blockIdx.x, h = blockIdx.y;
+    // Workgroups go to the eight XCDs in turn.  With a multiple of 8 heads, XCD x takes Hq / 8 consecutive
+    // heads; it walks them kv group by kv group, and inside a group query tile by query tile with the group's
+    // heads next to each other: the workgroups that run on an XCD at the same time then read the K and V of
+    // one kv head (of a few sequences) and find them in that XCD's L2.  (Dealt out head by head across the
+    // XCDs, every L2 fetched every K and V: 2.6 times the algorithmic traffic, and 11 % (MHA) to 21 % (8
+    // query heads per kv head) more time.)
+    int item, h;
+    if ((Hq & 7) == 0) {
+        const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+        const int hpx = Hq >> 3, G = Hq / kv.Hkv;
+        const int gl = G < hpx ? G : hpx;                    // heads of one kv group on this XCD
+        const int per_group = bv.n_prefill_items * gl;
+        const int grp = seq / per_group, r = seq - grp * per_group;
+        item = r / gl;
+        h = xcd * hpx + grp * gl + (r - item * gl);
+    } else {
+        h = blockIdx.x / bv.n_prefill_items;
+        item = blockIdx.x % bv.n_prefill_items;
+    }
     const int s = bv.prefill_items[2 * item], qt = bv.prefill_items[2 * item + 1];
     const int q0 = bv.q_start[s];
     const int qlen = bv.q_start[s + 1] - q0;
@@ -225,7 +243,7 @@ static void launch_prefill_d(const act_t* qkv, act_t* out, const BatchView& bv, 
         attr_set = true;
     }
     const float scale_log2 = kLog2e / sqrtf((float)D);
-    hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(bv.n_prefill_items, Hq), dim3(256), kLds, st, qkv, out, bv, kv, Hq,
+    hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(bv.n_prefill_items * Hq), dim3(256), kLds, st, qkv, out, bv, kv, Hq,
                        scale_log2);
 }
 
