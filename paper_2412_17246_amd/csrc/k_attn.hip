@@ -64,7 +64,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
     if ((Hq & 7) == 0) {
         const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
         const int hpx = Hq >> 3, G = Hq / kv.Hkv;
-        const int gl = G < hpx ? G : hpx;                    // heads of one kv group on this XCD
+        // heads of one kv group that sit next to each other on this XCD (1 if groups do not tile its heads)
+        const int gl = G >= hpx ? hpx : (hpx % G == 0 ? G : 1);
         const int per_group = bv.n_prefill_items * gl;
         const int grp = seq / per_group, r = seq - grp * per_group;
         item = r / gl;

@@ -191,6 +191,8 @@ MIX = W.DecoderShape("mix", L=2, H=512, Hq=8, Hkv=2, d=128, F=1024, rope_base=50
 MIX64 = W.DecoderShape("mix64", L=2, H=256, Hq=4, Hkv=2, d=64, F=512, rope_base=10000.0, seed=22)
 MHA = W.DecoderShape("mha", L=1, H=512, Hq=4, Hkv=4, d=128, F=768, rope_base=10000.0, seed=23)
 G8 = W.DecoderShape("g8", L=1, H=1024, Hq=8, Hkv=1, d=128, F=512, rope_base=500000.0, seed=24)
+# 24 query heads in 12 kv groups: three heads per XCD, which the groups of two do not tile
+H24 = W.DecoderShape("h24", L=1, H=768, Hq=24, Hkv=12, d=64, F=512, rope_base=10000.0, seed=25)
 
 
 def _mixed_case(torch, s, fp32, seqs):
@@ -231,7 +233,7 @@ def _mixed_case(torch, s, fp32, seqs):
 
 
 @pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
-@pytest.mark.parametrize("shape", [MIX, MIX64, MHA, G8], ids=lambda s: s.name)
+@pytest.mark.parametrize("shape", [MIX, MIX64, MHA, G8, H24], ids=lambda s: s.name)
 def test_mixed_ragged_batch(torch, fp32, shape):
     # prefill of several tiles + ragged tail, a 1-token prefill-from-empty, chunked prefill on top of
     # a cache, an empty sequence, and decode tokens whose caches straddle the 256-position chunks
