@@ -70,7 +70,7 @@ struct bz_instance {
     // the down projection waits for ev[l].  parts_valid[l] says whether the current load recorded them.
     std::vector<hipEvent_t> ev_part;
     std::vector<hipEvent_t> ev_part2;            // [4l + p]: the second stream's half of tensor group p of layer l
-    std::vector<char> parts_valid;
+    std::vector<char> parts_valid;               // 0: no group events for the current load; 1 / 2: recorded on one / two streams
     hipEvent_t t0 = nullptr;
     bool clock_started = false;
     bz::KvSlots* slots = nullptr;

@@ -226,16 +226,17 @@ int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpy
             HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy2));
             off += m;
         }
-        HIP_TRY(hipEventRecord(I->ev_part2[4 * layer + part], I->copy2));
+        const bool two = I->ingest_streams == 2;
+        if (two) HIP_TRY(hipEventRecord(I->ev_part2[4 * layer + part], I->copy2));
         if (part < 3) {
             HIP_TRY(hipEventRecord(I->ev_part[3 * layer + part], I->copy));
         } else {
-            HIP_TRY(hipStreamWaitEvent(I->copy, I->ev_part2[4 * layer + part], 0));
+            if (two) HIP_TRY(hipStreamWaitEvent(I->copy, I->ev_part2[4 * layer + part], 0));
             HIP_TRY(hipEventRecord(I->ev[layer], I->copy));
         }
         start = ends[part];
     }
-    I->parts_valid[layer] = 1;
+    I->parts_valid[layer] = (char)I->ingest_streams;     // 1: group events on the copy stream only; 2: on both streams
     I->state[layer] = kLoading;
     I->stats.bytes_ingested += n;
     I->stats.layers_requested += 1;
@@ -786,7 +787,8 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         const bool gated = I->state[l] != kResident;
         const bool by_part = gated && I->parts_valid[l] && l == b - 1;
         if (gated) HIP_TRY(hipStreamWaitEvent(st, by_part ? I->ev_part[3 * l] : I->ev[l], 0));
-        if (by_part) HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l], 0));
+        const bool two = by_part && I->parts_valid[l] == 2;
+        if (two) HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l], 0));
         const unsigned char* wl = layer_ptr(I, l);
         const bf16* g1 = (const bf16*)(wl + I->lay.g1);
         const bf16* wqkv = (const bf16*)(wl + I->lay.wq);
@@ -821,7 +823,7 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         int ks_o = 0;
         if (by_part) {
             HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 1], 0));
-            HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l + 1], 0));
+            if (two) HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l + 1], 0));
         }
         { ProfScope p(I, BZ_K_GEMM_O, 2.0 * T * sh.H * qd, (2.0 * T * sh.H + (double)T * qd) * e + 2.0 * sh.H * qd);
           ks_o = launch_gemm_partial(1, attn, wo, T, sh.H, qd, gws, gwsb, st);
@@ -831,7 +833,7 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
           else launch_rmsnorm(x, g2, normed, T, sh.H, I->cfg.rms_eps, st); }
         if (by_part) {
             HIP_TRY(hipStreamWaitEvent(st, I->ev_part[3 * l + 2], 0));
-            HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l + 2], 0));
+            if (two) HIP_TRY(hipStreamWaitEvent(st, I->ev_part2[4 * l + 2], 0));
         }
         { ProfScope p(I, BZ_K_GEMM_GATEUP, 4.0 * T * sh.F * sh.H, ((double)T * sh.H + (double)T * sh.F) * e + 4.0 * sh.F * sh.H);
           launch_gemm(2, normed, wgu, nullptr, act, T, sh.F, sh.H, gws, gwsb, st); }
