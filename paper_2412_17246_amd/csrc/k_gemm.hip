@@ -1008,7 +1008,11 @@ struct SkinnyPlan {
 template <int RB, int TB>
 static void skinny_plan_rb(SkinnyPlan& p, int Nrows, int nk, int m_blocks) {
     constexpr int kTile = 64 * RB;
-    const int kSlots = SkCfg<RB, TB>::kSlots / m_blocks;   // units the chip holds at a time
+    // Units one round hands out.  The long streams fill every workgroup slot of the chip.  The short ones (64-row tiles
+    // over at most 64 tokens) aim at one unit per CU although two fit: half as many K slices halve the partial sums
+    // written here and re-read by the consumer (8B decode at 64 tokens: qkv 17.7 -> 16.5 us, o 14.8 -> 12.0 us; a
+    // target of 128 or 192 units is slower again, 384 and more as well).
+    const int kSlots = ((RB == 1 && TB == 1) ? 256 : SkCfg<RB, TB>::kSlots) / m_blocks;
     p.rb = RB;
     p.tb = TB;
     p.m_blocks = m_blocks;
