@@ -140,3 +140,49 @@ def test_no_plan_finishes_earlier_on_uniform_topologies(n_src, n_tgt):
             for c in chains)
         for chains in _all_plans(list(range(n_src)), [10 + i for i in range(n_tgt)]))
     assert greedy == pytest.approx(best, rel=1e-12)
+
+
+def _finish(by, chains, L, layer, oversub):
+    return max(max(P.chain_ready_times([P.link_bw(by[c[k]], by[c[k + 1]], oversub) for k in range(len(c) - 1)], L, layer))
+               for c in chains)
+
+
+def test_spare_with_the_faster_link_is_chosen_when_fewer_targets_than_spares():
+    # two spares under the source's leaf, one target wanted: of the two single-hop plans the one to the
+    # spare with the faster link is ready first, and that is the plan generated
+    L, layer = 16, 0.5 * GB
+    nodes = [_node(0, P.SOURCE, gpus=4), _node(1, P.SPARE, gpus=1), _node(2, P.SPARE, gpus=4), _node(3, P.SPARE, gpus=2)]
+    by = {n.id: n for n in nodes}
+    times = {t: _finish(by, [[0, t]], L, layer, 1.0) for t in (1, 2, 3)}
+    plan = P.generate(nodes, 1)
+    assert plan.chains == [[0, min(times, key=times.get)]] == [[0, 2]]
+    # with two wanted, the slowest spare stays out
+    assert sorted(P.generate(nodes, 2).chains[0][1:]) == [2, 3]
+
+
+def test_target_on_a_leaf_without_sources_hangs_off_the_root_that_reaches_it_fastest():
+    # sources on leaves 0 and 1 (one GPU and four GPUs), a four-GPU target on leaf 2: across the spine the
+    # four-GPU source reaches it four times as fast, and brute force over both roots agrees
+    L, layer, over = 16, 0.5 * GB, 2.0
+    nodes = [_node(0, P.SOURCE, gpus=1, leaf=0), _node(1, P.SOURCE, gpus=4, leaf=1), _node(2, P.SPARE, gpus=4, leaf=2)]
+    by = {n.id: n for n in nodes}
+    times = {r: _finish(by, [[r, 2]], L, layer, over) for r in (0, 1)}
+    assert times[1] == pytest.approx(times[0] / 4)
+    plan = P.generate(nodes, 1, oversub=over)
+    assert plan.chains == [[1, 2]]
+    assert plan.hop_bw == [[4 * 25 * GB / over]]
+
+
+def test_equal_roots_share_remote_targets_instead_of_stacking_them_on_one_chain():
+    # two equal sources, two equal targets on leaves of their own: one target per root finishes one layer
+    # time earlier than both on one chain, and gives two tails (two live-scaling candidates)
+    L, layer, over = 8, 1.0 * GB, 2.0
+    nodes = [_node(0, P.SOURCE, leaf=0), _node(1, P.SOURCE, leaf=1), _node(2, P.SPARE, leaf=2), _node(3, P.SPARE, leaf=3)]
+    by = {n.id: n for n in nodes}
+    plan = P.generate(nodes, 2, oversub=over)
+    assert plan.chains == [[0, 2], [1, 3]] and plan.tails == [2, 3]
+    best = min(_finish(by, chains, L, layer, over) for chains in _all_plans([0, 1], [2, 3]))
+    stacked = _finish(by, [[0, 2, 3]], L, layer, over)
+    mine = max(P.plan_ready_times(plan, L, layer).values())
+    assert mine == pytest.approx(best, rel=1e-12)
+    assert stacked - mine == pytest.approx(layer / (25 * GB / over), rel=1e-9)

@@ -61,7 +61,9 @@ def _check_schedule(s, L, n, load_time):
 
 
 @pytest.mark.parametrize("L,n,load,free", [(7, 7, 6, 1), (4, 3, 2, 0), (8, 10, 3, 5), (5, 6, 0.5, 2), (6, 4, 10, 0),
-                                          (3, 8, 1, 1), (12, 5, 7, 30)])
+                                          (3, 8, 1, 1), (12, 5, 7, 30),
+                                          # the source becomes free in the middle of a layer of the target
+                                          (7, 5, 2, 1.5), (6, 6, 1, 0.25), (5, 4, 2.5, 3.75)])
 def test_invariants(L, n, load, free):
     _check_schedule(Z.simulate_zigzag(L, n, load, free), L, n, load)
     _check_schedule(Z.simulate_best_effort(L, n, load, free), L, n, load)
@@ -80,6 +82,10 @@ def test_limits_with_closed_forms():
     # an idle source at time 0 takes the first request whole (nothing has run on the target yet)
     s = Z.simulate_zigzag(L, 2, 3, source_free_at=0)
     assert (s.T[0], s.S[0], s.finish[0]) == (0, L, L)
+    # a source that becomes free while the target is inside layer 0 of the first request waits for that layer
+    # to end (it may not run it a second time): it takes the request at time 1 with L - 1 layers left
+    s = Z.simulate_zigzag(L, 1, 10 ** 6, source_free_at=0.5)
+    assert (s.T[0], s.S[0], s.finish[0]) == (1, L - 1, L)
     # best-effort never puts more than half of the layers on the target
     b = Z.simulate_best_effort(8, 6, 0, source_free_at=0)
     assert b.T == [4] * 6
