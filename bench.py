@@ -294,7 +294,7 @@ def run_decode(args, torch, Instance):
     if args.fixed_len:                    # every cache the same length (no short sequences, no ragged last chunks)
         lens = np.full(B, args.fixed_len, dtype=np.int64)
         lo = hi = args.fixed_len
-    n_steps = args.steps + args.warmup + 4
+    n_steps = 2 * args.steps + args.warmup + 4     # every step appends a position: profiled steps, then the timed ones
     stream = torch.cuda.Stream()
     gen = torch.Generator(device="cuda")
     gen.manual_seed(base.seed)
@@ -392,6 +392,7 @@ def run_decode(args, torch, Instance):
     t0 = time.perf_counter()
     for st in range(args.steps):
         inst.run_layers(0, shape.L, batch, xs[st % n_steps])
+        inst.batch_advance(batch)
     inst.sync()
     plain = time.perf_counter() - t0
 
