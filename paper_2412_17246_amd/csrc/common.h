@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "blitz_layer.h"
 
 namespace bz {
@@ -22,6 +24,31 @@ typedef bf16 act_t;
 #endif
 
 constexpr int kWave = 64;
+
+// A kernel's dynamic-LDS limit is a per-function, per-device setting.  One of these per kernel
+// instantiation remembers on which devices the limit has been raised (or refused), so that the call is
+// made once per device; threads that race here make the same idempotent call.  A refusal is consumed
+// here and reported as false, never by a later HIP call.
+struct LdsLimit {
+    std::atomic<uint64_t> granted{0}, refused{0};
+    bool raise(const void* fn, int bytes) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return false;
+        }
+        const uint64_t bit = (dev >= 0 && dev < 64) ? (uint64_t)1 << dev : 0;    // devices past 63: asked every time
+        if (granted.load(std::memory_order_acquire) & bit) return true;
+        if (refused.load(std::memory_order_acquire) & bit) return false;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            refused.fetch_or(bit, std::memory_order_release);
+            return false;
+        }
+        granted.fetch_or(bit, std::memory_order_release);
+        return true;
+    }
+};
 
 // ---- 8-element loads / stores, converting to and from float --------------------------------
 __device__ __forceinline__ void load8(const bf16* p, float (&v)[8]) {

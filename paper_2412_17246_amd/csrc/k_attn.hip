@@ -237,12 +237,8 @@ template <int D>
 static void launch_prefill_d(const act_t* qkv, act_t* out, const BatchView& bv, const KvView& kv, int Hq,
                              hipStream_t st) {
     constexpr int kLds = 2 * 4 * 32 * D * (int)sizeof(bf16);     // two stages of (K tile + V tile)
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_kernel<D>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        attr_set = true;
-    }
+    static LdsLimit limit;
+    (void)limit.raise(reinterpret_cast<const void*>(attn_prefill_kernel<D>), kLds);
     const float scale_log2 = kLog2e / sqrtf((float)D);
     hipLaunchKernelGGL(attn_prefill_kernel<D>, dim3(bv.n_prefill_items * Hq), dim3(256), kLds, st, qkv, out, bv, kv, Hq,
                        scale_log2);
@@ -304,12 +300,8 @@ void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, cons
     if (bv.n_prefill_items <= 0) return;
     const float scale_log2 = kLog2e / sqrtf((float)kv.d);
     // 64 KiB of LDS holds 16384 scores: enough for every supported max_seq_len in the debug build
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_naive_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
-        attr_set = true;
-    }
+    static LdsLimit limit;
+    (void)limit.raise(reinterpret_cast<const void*>(attn_naive_kernel), 65536);
     hipLaunchKernelGGL(attn_naive_kernel, dim3(bv.T, Hq), dim3(64), 65536, st, qkv, out, bv, kv, Hq, scale_log2);
 }
 #endif

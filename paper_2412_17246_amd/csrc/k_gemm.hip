@@ -697,21 +697,15 @@ static bool big_ok(int M, int N, int K) {
            (uint64_t)2 * N * K < 0x7fffffffull;          // the large-tile kernel uses 32-bit byte offsets / 2
 }
 
-// The large-tile kernel needs the CU's whole 160 KiB of LDS; if the runtime does not grant it (it is a
-// property of the device, asked once per instantiation) the caller takes the 128x128 kernel instead.
+// The large-tile kernel needs the CU's whole 160 KiB of LDS; if the runtime does not grant it (asked once per
+// instantiation and device) the caller takes the 128x128 kernel instead.
 template <int MODE>
 static bool big_available() {
     constexpr int LDS = kBigSlots * kBigSlot;
-    static int state = 0;                               // 0 not asked yet, 1 granted, -1 refused
-    if (state == 0) {
-        const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, false>),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, true>),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        state = (e1 == hipSuccess && e2 == hipSuccess) ? 1 : -1;
-        if (state < 0) (void)hipGetLastError();         // the refusal is handled here, not reported by a later call
-    }
-    return state > 0;
+    static LdsLimit whole, partial;
+    const bool a = whole.raise(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, false>), LDS);
+    const bool b = partial.raise(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, true>), LDS);
+    return a && b;
 }
 
 template <int MODE>
@@ -1084,12 +1078,8 @@ struct SkinnyArgs {
 template <bool GU, bool NT, int RB, int TB>
 static void skinny_go(dim3 grid, hipStream_t st, const SkinnyArgs& g) {
     constexpr int lds = SkCfg<RB, TB>::kLds;
-    static bool raised = false;          // per instantiation: the LDS limit is a per-function setting
-    if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<GU, NT, RB, TB>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        raised = true;
-    }
+    static LdsLimit limit;               // per instantiation: the LDS limit is a per-function setting
+    (void)limit.raise(reinterpret_cast<const void*>(gemm_skinny_kernel<GU, NT, RB, TB>), lds);
     hipLaunchKernelGGL((gemm_skinny_kernel<GU, NT, RB, TB>), grid, dim3(256), lds, st, g.a, g.w, g.ws, g.direct, g.M,
                        g.Nrows, g.K, g.n_tiles, g.kt_per_split, g.rows, g.m_blocks, g.units);
 }
@@ -1142,11 +1132,8 @@ static void launch_cfg(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
     constexpr int OUT_BN = (MODE == 2) ? BN / 2 : BN;
     constexpr int LDS = gemm_lds_bytes<BM, BN>();
     auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, MODE>;
-    static bool attr_set = false;      // one attribute per instantiation
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        attr_set = true;
-    }
+    static LdsLimit limit;             // one per instantiation
+    (void)limit.raise(reinterpret_cast<const void*>(kern), LDS);
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + OUT_BN - 1) / OUT_BN;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), LDS, st, a, w, r, c, M, N, K,
                        tiles_m, tiles_n);
