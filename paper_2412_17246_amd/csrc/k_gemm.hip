@@ -449,8 +449,9 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
     for (int ks = 0; ks < 4; ++ks) k_off[ks] = ((ks * 2 + lk) ^ sw) * 16;
 
     // ---- main loop.  Every k-step is NMMA MFMAs in a fixed order; between them, one by one, go the
-    // LDS reads that fetch the operands of the NEXT k-step and, after every fourth MFMA, one
-    // global->LDS load.  The order is pinned with scheduling barriers so the matrix pipe never waits
+    // LDS reads that fetch the operands of the NEXT k-step (first half of the k-step) and, after every
+    // second MFMA of the other half, one global->LDS load (a load behind an MFMA that already has an LDS
+    // read behind it makes the next MFMA late: 1-2.5 % on the four projections).  The order is pinned with scheduling barriers so the matrix pipe never waits
     // behind a burst of memory instructions.  The tile barrier sits before the last k-step, whose
     // operands are already in registers; it is a bare s_barrier (the waits are written out here; a
     // full __syncthreads would drain the loads that are meant to stay in flight).
@@ -466,7 +467,8 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         else wf[buf][q - 4] = *reinterpret_cast<const bf16x8*>(sw_ + w_off[q - 4] + k_off[ks]);
     };
     constexpr int PER = NCH / 2;                       // loads per wave per k-step
-    constexpr int GAP = NMMA / PER;                    // MFMAs between two loads of a wave
+    constexpr int LGAP = (NMMA - NFETCH) / PER;        // MFMAs between two loads of a wave
+    static_assert(LGAP >= 1 && LGAP * PER == NMMA - NFETCH, "the loads of a k-step go behind its LDS reads");
     // one k-step: MFMAs from buffer `cur`; fetch k-step `nks` of the tile in slots (sx, sw_) into the
     // other buffer; request pieces p0 .. p0 + PER - 1 of one operand of k-tile `ikt` into slot `islot`
     auto kstep = [&](int cur, const unsigned char* sx, const unsigned char* sw_, int nks, int ikt, int islot, bool iweights,
@@ -477,7 +479,7 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
             const int j = q >> 2, i = q & 3;
             acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][j], xf[cur][i], acc[j][i], 0, 0, 0);
             if (q < NFETCH) fetch_piece(sx, sw_, nks, cur ^ 1, q);
-            if (q % GAP == GAP - 1) issue_piece(ikt, islot, iweights, p0 + q / GAP);
+            if (q >= NFETCH && (q - NFETCH) % LGAP == LGAP - 1) issue_piece(ikt, islot, iweights, p0 + (q - NFETCH) / LGAP);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
