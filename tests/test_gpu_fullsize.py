@@ -1,5 +1,5 @@
 """Parity at the real shapes, in the launch configurations the benchmark times: one decoder layer of
-the 7B and 8B-GQA shapes, teacher-forced with seeded inputs, against the CPU oracle.  Where the
+the 7B, 8B-GQA, 13B and 70B shapes, teacher-forced with seeded inputs, against the CPU oracle.  Where the
 whole output is too expensive for the oracle, sampled sequences are compared (the oracle computes a
 sequence on its own exactly as it does inside a batch)."""
 import numpy as np
@@ -143,3 +143,108 @@ def test_7b_layer_run_enqueued_while_its_weights_arrive(torch, streams):
     assert torch.equal(x1.view(torch.int16), x2.view(torch.int16))
     assert np.array_equal(inst.readback_layer(0), blob.numpy())
     inst.close()
+
+
+def test_13b_layer_mixed_bench_batch_sampled_sequences(torch):
+    """The mixed batch of the 13B-shaped configuration as the benchmark builds it (16 prefill requests with
+    lognormal lengths plus 48 decode sequences with seeded caches: about 12 k rows in one call, prefill and
+    decode attention side by side).  The oracle recomputes the shortest prefill request, the first 96 tokens
+    of the longest one, and the decode sequences with the shortest and the longest cache."""
+    base = W.CONFIGS["13b"]
+    s = _one_layer_shape(base)
+    p_lens = W.lognormal_lengths(base.seed, 16, 768.0, 0.6, 32, 4096)
+    d_lens = W.uniform_lengths(base.seed, 48, 128, 2048)
+    lens_new = [int(n) for n in p_lens] + [1] * 48
+    befores = [0] * 16 + [int(n) for n in d_lens]
+    q_start = np.concatenate([[0], np.cumsum(lens_new)]).astype(np.int64)
+    T, B = int(q_start[-1]), len(lens_new)
+    caps = [n + b for n, b in zip(lens_new, befores)]
+    bits = W.layer_weights_bits(base, 0)
+    inst = U.make_instance(s, max_seqs=B, max_seq_len=max(caps) + 1, max_tokens=T, kv_tokens=sum(caps) + 32 * B)
+    for i, c in enumerate(caps):
+        inst.kv_reserve(i, c)
+    d_short, d_long = 16 + int(np.argmin(d_lens)), 16 + int(np.argmax(d_lens))
+    okv = O.OracleKV()
+    for i in range(16, B):
+        kb, vb = W.kv_prefill_bits(base, 0, i, befores[i])
+        inst.kv_write(0, i, 0, befores[i], kb, vb)
+        if i in (d_short, d_long):
+            okv.put(0, i, U.f64(kb), U.f64(vb))
+    inst.load_layer(0, inst.pinned_blob(inst.pack_layer(bits)))
+    xbits = W.hidden_bits(base, T, step=0)
+    x = U.to_device(xbits, False)
+    torch.cuda.synchronize()
+    inst.run_layers(0, 1, inst.batch(q_start, list(range(B)), befores), x)
+    inst.sync()
+    got = U.from_device(x)
+    inst.close()
+    assert np.all(np.isfinite(got))
+    wts = {0: U.oracle_weights(bits)}
+    osh = U.oracle_shape(s)
+    p_short, p_long = int(np.argmin(p_lens)), int(np.argmax(p_lens))
+    for seq, n in ((p_short, int(p_lens[p_short])), (p_long, 96)):
+        a = int(q_start[seq])
+        want = O.run_layers(osh, wts, 0, 1, U.f64(xbits[a:a + n]), O.OracleBatch([0, n], [0], [0]), O.OracleKV())
+        err = U.rel_err(got[a:a + n], want)
+        assert err <= U.BF16_TOL, (seq, err)
+    for seq in (d_short, d_long):
+        a = int(q_start[seq])
+        want = O.run_layers(osh, wts, 0, 1, U.f64(xbits[a:a + 1]), O.OracleBatch([0, 1], [seq], [befores[seq]]), okv)
+        err = U.rel_err(got[a:a + 1], want)
+        assert err <= U.BF16_TOL, (seq, err)
+
+
+def test_70b_layer_decode_step_and_prefill_sampled(torch):
+    """One layer of the 70B shape (8 query heads per kv head, 28672-wide MLP: every projection is a long
+    weight stream).  A decode step of 32 sequences with caches uniform[512, 4096], whole output against the
+    oracle; then a 4 x 2048-token prefill batch through the same layer, the first 64 tokens of two requests
+    recomputed by the oracle."""
+    base = W.CONFIGS["70b"]
+    s = _one_layer_shape(base)
+    B = 32
+    lens = W.uniform_lengths(base.seed, B, 512, 4096)
+    bits = W.layer_weights_bits(base, 0)
+    wts = {0: U.oracle_weights(bits)}
+    osh = U.oracle_shape(s)
+    inst = U.make_instance(s, max_seqs=B, max_seq_len=4097 + 1, max_tokens=4 * 2048,
+                           kv_tokens=int(lens.sum()) + 33 * B + 4 * 2048 + 128)
+    okv = O.OracleKV()
+    for i, n in enumerate(lens):
+        n = int(n)
+        inst.kv_reserve(i, n + 1)
+        kb, vb = W.kv_prefill_bits(base, 0, i, n)
+        inst.kv_write(0, i, 0, n, kb, vb)
+        okv.put(0, i, U.f64(kb), U.f64(vb))
+    inst.load_layer(0, inst.pinned_blob(inst.pack_layer(bits)))
+    xbits = W.hidden_bits(base, B, step=3)
+    x = U.to_device(xbits, False)
+    torch.cuda.synchronize()
+    q_start = list(range(B + 1))
+    befores = [int(n) for n in lens]
+    inst.run_layers(0, 1, inst.batch(q_start, list(range(B)), befores), x)
+    inst.sync()
+    got = U.from_device(x)
+    want = O.run_layers(osh, wts, 0, 1, U.f64(xbits), O.OracleBatch(q_start, list(range(B)), befores), okv)
+    err = U.rel_err(got, want)
+    assert err <= U.BF16_TOL, err
+    # prefill: 4 requests of 2048 tokens in fresh slots
+    for i in range(B):
+        inst.kv_release(i)
+    n_req, n_tok = 4, 2048
+    for i in range(n_req):
+        inst.kv_reserve(i, n_tok)
+    T = n_req * n_tok
+    xbits = W.hidden_bits(base, T, step=4)
+    x = U.to_device(xbits, False)
+    torch.cuda.synchronize()
+    q_start = [i * n_tok for i in range(n_req + 1)]
+    inst.run_layers(0, 1, inst.batch(q_start, list(range(n_req)), [0] * n_req), x)
+    inst.sync()
+    got = U.from_device(x)
+    inst.close()
+    assert np.all(np.isfinite(got))
+    for seq in (0, 3):
+        a, n = q_start[seq], 64
+        want = O.run_layers(osh, wts, 0, 1, U.f64(xbits[a:a + n]), O.OracleBatch([0, n], [0], [0]), O.OracleKV())
+        err = U.rel_err(got[a:a + n], want)
+        assert err <= U.BF16_TOL, (seq, err)
