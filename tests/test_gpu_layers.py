@@ -277,6 +277,19 @@ def test_long_caches(torch, fp32, shape):
         assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
 
 
+@pytest.mark.parametrize("shape", [MIX64, G8], ids=lambda s: s.name)
+def test_caches_of_tens_of_thousands_of_positions(torch, shape):
+    # far beyond the benchmark's 4096: a decode step over 70000 cached positions (274 chunks, 18 batches of
+    # partial results in the combine step; rotary angles up to 70000 * theta), two new tokens on top of 65535
+    # (the prefill kernel walks 1024 tiles of keys and ends one position past a power of two), a cache of
+    # exactly 32768, and a short neighbour so that the work list mixes 1-chunk and 274-chunk sequences
+    seqs = [(1, 70000), (2, 65535), (1, 32768), (1, 5)]
+    got, want, q_start = _mixed_case(torch, shape, False, seqs)
+    for i in range(len(seqs)):
+        a, b = q_start[i], q_start[i + 1]
+        assert U.rel_err(got[a:b], want[a:b]) <= U.BF16_TOL, (i, seqs[i])
+
+
 @pytest.mark.parametrize("extra", [0, 90], ids=["105rows", "195rows"])
 @pytest.mark.parametrize("shape", [MIX, G8], ids=lambda s: s.name)
 def test_mixed_batch_of_65_to_256_rows(torch, shape, extra):
