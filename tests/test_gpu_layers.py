@@ -277,6 +277,27 @@ def test_long_caches(torch, fp32, shape):
         assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
 
 
+ODD = [W.DecoderShape("odd264", L=2, H=264, Hq=3, Hkv=3, d=64, F=520, rope_base=10000.0, seed=31),
+       W.DecoderShape("odd328", L=2, H=328, Hq=6, Hkv=3, d=128, F=344, rope_base=500000.0, seed=32),
+       W.DecoderShape("odd1096", L=1, H=1096, Hq=16, Hkv=2, d=64, F=1000, rope_base=10000.0, seed=33)]
+
+
+@pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
+@pytest.mark.parametrize("rows", ["decode-sized", "hundreds"])
+@pytest.mark.parametrize("shape", ODD, ids=lambda s: s.name)
+def test_widths_that_are_no_multiple_of_a_tile(torch, fp32, shape, rows):
+    # hidden and MLP widths that are multiples of 8 only (every reduction dimension ends in a partial 64-wide
+    # k-tile, so the projections take the kernel with a K tail), 3, 6 and 16 query heads, all four group sizes
+    # between them; a decode-sized batch and one of a few hundred rows
+    seqs = [(5, 0), (1, 37), (1, 300), (2, 31), (1, 0)] if rows == "decode-sized" else \
+           [(150, 0), (1, 64), (97, 33), (1, 511), (40, 200)]
+    got, want, q_start = _mixed_case(torch, shape, fp32, seqs)
+    tol = _tol(fp32)
+    for i in range(len(seqs)):
+        a, b = q_start[i], q_start[i + 1]
+        assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
+
+
 @pytest.mark.parametrize("shape", [MIX64, G8], ids=lambda s: s.name)
 def test_caches_of_tens_of_thousands_of_positions(torch, shape):
     # far beyond the benchmark's 4096: a decode step over 70000 cached positions (274 chunks, 18 batches of
