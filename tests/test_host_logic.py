@@ -158,7 +158,9 @@ def test_scheduler_decisions_match_the_oracle_in_virtual_time():
     configurations and finish times must agree exactly, for both policies."""
     from oracle import zigzag as Z
     cases = [(7, 7, 6.0, 1.0), (4, 3, 2.0, 0.0), (8, 10, 3.0, 5.0), (5, 6, 0.5, 2.0), (6, 4, 10.0, 0.0),
-             (3, 8, 1.0, 1.0), (12, 5, 7.0, 30.0), (32, 12, 6.0, 1.0), (80, 6, 2.5, 0.0), (2, 2, 0.0, 0.0)]
+             (3, 8, 1.0, 1.0), (12, 5, 7.0, 30.0), (32, 12, 6.0, 1.0), (80, 6, 2.5, 0.0), (2, 2, 0.0, 0.0),
+             # the source becomes free while the target is inside a layer
+             (7, 5, 2.0, 1.5), (6, 6, 1.0, 0.25), (5, 4, 2.5, 3.75), (5, 1, 1e6, 0.5)]
     for L, n, load, free in cases:
         T, fin = B.zz_simulate(B.BZ_ZZ_ZIGZAG, L, n, load, free)
         want = Z.simulate_zigzag(L, n, load, free)
