@@ -5,6 +5,8 @@
 // is one 16-byte LDS read.  Tiles are staged global -> registers -> LDS, double buffered, one
 // barrier per 64-wide K step; LDS rows are padded by 16 bytes so the 16-byte operand reads of 16
 // consecutive rows fall in distinct banks.
+#include <type_traits>
+
 #include "common.h"
 
 namespace bz {
@@ -589,20 +591,24 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
 }
 
 // Adds the partial tiles of one split tile in range order and applies the epilogue.  One wave per
-// (wave of the main kernel, feature block j, token block i, register group g): a lane sums the 4
-// values behind one 8-byte output store.  Loads of eight ranges go out together (a range index past
-// the end re-reads the last range; its value is not added).  Grid (split tiles, units / 4).
-template <int MODE, int WN>
+// (wave of the main kernel, feature block j, token block i, piece of the block's 16 registers): a lane sums
+// the values behind one output store, 8 consecutive features (registers 8p..8p+7, a 16-byte store) when
+// WIDE - rows of N % 8 == 0 features - else 4 (registers 4g..4g+3).  The ranges are taken four at a time,
+// then two, then one, every batch's loads going out together; the sums run in range order whatever the
+// batching.  Grid (split tiles, units / 4).
+template <int MODE, int WN, bool WIDE>
 __global__ __launch_bounds__(256) void gemm_big_fixup(const float* __restrict__ ws, const bf16* R, bf16* C, int M,
                                                       int N, int tiles_m, int tiles_n, int n_dp, int splits) {
     constexpr int NJ = 8 / WN;
     constexpr int NJE = (MODE == 2) ? NJ / 2 : NJ;      // output blocks per wave of the main kernel
     constexpr int NV = (MODE == 2) ? 2 : 1;             // accumulator blocks behind one output block
+    constexpr int GV = WIDE ? 8 : 4;                    // values per lane and accumulator block
+    constexpr int PB = WIDE ? 1 : 2;                    // bits of the piece index
     const int tile = blockIdx.x;
     const BigTile bt = big_tile_of<MODE>(n_dp + tile, tiles_m, tiles_n);
     const int lane = threadIdx.x & 63;
     const int u = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int g = u & 3, i = (u >> 2) & 3, j = (u >> 4) % NJE, wave = (u >> 4) / NJE;
+    const int piece = u & ((1 << PB) - 1), i = (u >> PB) & 3, j = (u >> (PB + 2)) % NJE, wave = (u >> (PB + 2)) / NJE;
     const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane & 31, lk = lane >> 5;
     int fbase[NJ], wrow[NJ];
@@ -612,49 +618,64 @@ __global__ __launch_bounds__(256) void gemm_big_fixup(const float* __restrict__ 
     for (int jj = 0; jj < NJE; ++jj) fb = (jj == j) ? fbase[jj] : fb;
     if (bt.m0 + wm * 128 + i * 32 >= M) return;          // block past the last row: nothing was stored for it
     const int m = bt.m0 + wm * 128 + i * 32 + lrow;
-    const int n = bt.n0 + fb + big_group_feature(g, lk);
-    float acc[NV][4];
+    const int n = bt.n0 + fb + (WIDE ? 16 * piece + 8 * lk : big_group_feature(piece, lk));
+    // the residual does not depend on the sums: requested first (rows and features past the end: a valid
+    // address, value unused)
+    bf16x8 rv8;
+    bf16x4 rv4;
+    if (MODE == 1) {
+        const int mc = m < M ? m : M - 1;
+        int nc = n;
+        if (nc > N - GV) nc = N - GV;
+        if (WIDE) rv8 = *reinterpret_cast<const bf16x8*>(R + (size_t)mc * N + nc);
+        else rv4 = *reinterpret_cast<const bf16x4*>(R + (size_t)mc * N + nc);
+    }
+    float acc[NV][GV];
 #pragma unroll
     for (int v = 0; v < NV; ++v)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[v][e] = 0.f;
+        for (int e = 0; e < GV; ++e) acc[v][e] = 0.f;
     const float* base = ws + (size_t)tile * splits * 65536 + (size_t)wave * NJ * 4 * 16 * 64 + lane;
-    for (int s0 = 0; s0 < splits; s0 += 8) {
-        float t[8][NV][4];
+    auto batch = [&](int s0, auto nb) {
+        constexpr int NB = decltype(nb)::value;
+        float t[NB][NV][GV];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int sidx = (s0 + q < splits) ? s0 + q : splits - 1;
+        for (int q = 0; q < NB; ++q)
 #pragma unroll
             for (int v = 0; v < NV; ++v)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    t[q][v][e] = base[(size_t)sidx * 65536 + (((j + v * (NJ / 2)) * 4 + i) * 16 + 4 * g + e) * 64];
-        }
+                for (int e = 0; e < GV; ++e)
+                    t[q][v][e] = base[(size_t)(s0 + q) * 65536 + (((j + v * (NJ / 2)) * 4 + i) * 16 + GV * piece + e) * 64];
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            if (s0 + q < splits)
+        for (int q = 0; q < NB; ++q)
 #pragma unroll
-                for (int v = 0; v < NV; ++v)
+            for (int v = 0; v < NV; ++v)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[v][e] += t[q][v][e];
-    }
+                for (int e = 0; e < GV; ++e) acc[v][e] += t[q][v][e];
+    };
+    int s0 = 0;
+    for (; s0 + 4 <= splits; s0 += 4) batch(s0, std::integral_constant<int, 4>());
+    if (s0 + 2 <= splits) { batch(s0, std::integral_constant<int, 2>()); s0 += 2; }
+    if (s0 < splits) batch(s0, std::integral_constant<int, 1>());
     if (m >= M || n >= N) return;
-    bf16x4 o;
-    if (MODE == 2) {
+    float o[GV];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float gt = acc[0][e], up = acc[NV - 1][e];
-            o[e] = (bf16)(silu_fast(gt) * up);
-        }
-    } else if (MODE == 1) {
-        const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[0][e] + (float)rv[e]);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16)acc[0][e];
+    for (int e = 0; e < GV; ++e) {
+        if (MODE == 2) o[e] = silu_fast(acc[0][e]) * acc[NV - 1][e];
+        else if (MODE == 1) o[e] = acc[0][e] + (float)(WIDE ? rv8[e] : rv4[e]);
+        else o[e] = acc[0][e];
     }
-    *reinterpret_cast<bf16x4*>(C + (size_t)m * N + n) = o;
+    if (WIDE) {
+        bf16x8 w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = (bf16)o[e];
+        *reinterpret_cast<bf16x8*>(C + (size_t)m * N + n) = w;
+    } else {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16)o[e];
+        *reinterpret_cast<bf16x4*>(C + (size_t)m * N + n) = w;
+    }
 }
 
 struct BigPlan {
@@ -729,8 +750,12 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
         hipLaunchKernelGGL(kern_part, dim3(p.tail * p.splits), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K,
                            p.tiles_m, p.tiles_n, p.n_dp, p.splits, ws);
         constexpr int kUnits = 2 * BZ_BIG_WN * ((MODE == 2) ? 4 / BZ_BIG_WN : 8 / BZ_BIG_WN) * 16;   // waves * blocks * (i, g)
-        hipLaunchKernelGGL((gemm_big_fixup<MODE, BZ_BIG_WN>), dim3(p.tail, kUnits / 4), dim3(256), 0, st, ws, r, c, M, N,
-                           p.tiles_m, p.tiles_n, p.n_dp, p.splits);
+        if ((N & 7) == 0)
+            hipLaunchKernelGGL((gemm_big_fixup<MODE, BZ_BIG_WN, true>), dim3(p.tail, kUnits / 8), dim3(256), 0, st, ws, r, c,
+                               M, N, p.tiles_m, p.tiles_n, p.n_dp, p.splits);
+        else
+            hipLaunchKernelGGL((gemm_big_fixup<MODE, BZ_BIG_WN, false>), dim3(p.tail, kUnits / 4), dim3(256), 0, st, ws, r, c,
+                               M, N, p.tiles_m, p.tiles_n, p.n_dp, p.splits);
     }
 }
 
