@@ -164,8 +164,8 @@ int bz_layer_layout_of(const bz_config* cfg, bz_layer_layout* out);
  * off the scaling path (appendix A.1, pre-created contexts), so it is outside any TTFT figure.
  * Adopted arenas and streams stay owned by the caller and must outlive the instance. */
 int bz_create(const bz_config* cfg, bz_instance** out);
-int bz_destroy(bz_instance* inst);               /* waits for both streams, frees what the library allocated */
-int bz_sync(bz_instance* inst);                  /* waits for both streams */
+int bz_destroy(bz_instance* inst);               /* waits for the instance's streams, frees what the library allocated */
+int bz_sync(bz_instance* inst);                  /* waits for the copy streams, then for the compute stream */
 
 /* Layer ingest (section 4: load the next layers while loaded ones execute; section 5.1: layers
  * arrive one by one).  Enqueues chunked async copies of `n` == layer_bytes bytes from pinned host
@@ -205,7 +205,7 @@ typedef struct bz_shard {
     int32_t     reserved_;
 } bz_shard;
 int bz_load_layer_sharded(bz_instance* inst, int layer, const bz_shard* shards, int n_shards);
-/* Forgets layer i (waits for both streams first); it must be loaded again before it can run. */
+/* Forgets layer i (waits for the instance's streams first); it must be loaded again before it can run. */
 int bz_unload_layer(bz_instance* inst, int layer);
 
 /* Number k of leading layers [0,k) that are resident now.  Never blocks. */
@@ -261,9 +261,12 @@ int bz_batch_advance(bz_instance* inst, bz_batch* batch);
  * bz_load_layer_from_device, each of its stages waits only for the tensors it reads (QKV group
  * before the first norm, wo and the second norm's gain before the output projection, gate/up
  * before the MLP, the whole layer before the down projection), so its attention runs while its
- * MLP weights arrive.  A sharded layer is waited for as a whole.  With BZ_RUN_NOWAIT it returns BZ_ENOTREADY instead if any layer of [a,b) is not
- * resident yet.  Results do not depend on a, b, the frontier or timing: running [a,k) then [k,b)
- * (on this or another instance holding the same weights) is bit-identical to running [a,b). */
+ * MLP weights arrive.  A sharded layer is waited for as a whole.  With BZ_RUN_NOWAIT the call
+ * returns BZ_ENOTREADY instead if any layer of [a,b) is not resident yet.  Results do not depend on
+ * a, b, the frontier or timing: running [a,k) then [k,b) (on this or another instance holding the
+ * same weights) is bit-identical to running [a,b).
+ * BZ_ENOTLOADED if a layer of [a,b) was never requested, BZ_ECAPACITY if the batch has more rows than
+ * max_tokens or a sequence outgrows its slot, BZ_ESTATE if a slot of the batch is not reserved. */
 int bz_run_layers(bz_instance* inst, int a, int b, const bz_batch* batch, void* hidden, int flags);
 
 /* Activation hand-off at a layer boundary (section 4: the scaled instance "forwards the
@@ -340,8 +343,9 @@ int bz_op_rmsnorm(const void* x, const void* gain, void* y, int T, int H, float 
  * `workspace`: device scratch of at least bz_op_gemm_workspace_bytes(mode, M, N, K) bytes, 16-byte
  * aligned.  Problems of up to 256 rows split K over workgroups and keep partial sums there;
  * larger ones whose tile count is below the number of compute units, or leaves a small last
- * round, split those tiles over K and keep partial tiles there.  With NULL or too small a workspace a schedule that needs none is used
- * (same result up to fp32 summation order); bz_run_layers always provides one. */
+ * round, split those tiles over K and keep partial tiles there.  With NULL or too small a workspace
+ * a schedule that needs none is used (same result up to fp32 summation order); bz_run_layers always
+ * provides one. */
 size_t bz_op_gemm_workspace_bytes(int mode, int M, int N, int K);
 int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K, void* workspace,
                size_t workspace_bytes, void* stream);
