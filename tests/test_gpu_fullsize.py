@@ -45,6 +45,7 @@ def test_7b_layer_small_ragged_batch_whole_output(torch, layer):
     want = O.run_layers(U.oracle_shape(s), {0: U.oracle_weights(bits)}, 0, 1, U.f64(xbits),
                         O.OracleBatch(q_start, [0, 1], [0, 0]), O.OracleKV())
     err = U.rel_err(got, want)
+    U.assert_rms(got, want, U.RMS_BF16_FULLSIZE)
     assert err <= U.BF16_TOL, err
 
 
@@ -76,6 +77,7 @@ def test_7b_layer_bench_batch_sampled_sequences(torch):
         a = int(q_start[seq])
         want = O.run_layers(osh, wts, 0, 1, U.f64(xbits[a:a + n]), O.OracleBatch([0, n], [0], [0]), O.OracleKV())
         err = U.rel_err(got[a:a + n], want)
+        U.assert_rms(got[a:a + n], want, U.RMS_BF16_FULLSIZE)
         assert err <= U.BF16_TOL, (seq, err)
     assert np.all(np.isfinite(got))
 
@@ -109,6 +111,7 @@ def test_8b_gqa_decode_step_full_batch(torch):
     want = O.run_layers(U.oracle_shape(s), {0: U.oracle_weights(bits)}, 0, 1, U.f64(xbits),
                         O.OracleBatch(q_start, list(range(B)), befores), okv)
     err = U.rel_err(got, want)
+    U.assert_rms(got, want, U.RMS_BF16_FULLSIZE)
     assert err <= U.BF16_TOL, err
     for i in (int(np.argmin(lens)), int(np.argmax(lens))):       # shortest and longest cache on their own
         assert U.rel_err(got[i:i + 1], want[i:i + 1]) <= U.BF16_TOL
@@ -186,11 +189,13 @@ def test_13b_layer_mixed_bench_batch_sampled_sequences(torch):
         a = int(q_start[seq])
         want = O.run_layers(osh, wts, 0, 1, U.f64(xbits[a:a + n]), O.OracleBatch([0, n], [0], [0]), O.OracleKV())
         err = U.rel_err(got[a:a + n], want)
+        U.assert_rms(got[a:a + n], want, U.RMS_BF16_FULLSIZE)
         assert err <= U.BF16_TOL, (seq, err)
     for seq in (d_short, d_long):
         a = int(q_start[seq])
         want = O.run_layers(osh, wts, 0, 1, U.f64(xbits[a:a + 1]), O.OracleBatch([0, 1], [seq], [befores[seq]]), okv)
         err = U.rel_err(got[a:a + 1], want)
+        U.assert_rms(got[a:a + 1], want, U.RMS_BF16_FULLSIZE)
         assert err <= U.BF16_TOL, (seq, err)
 
 
@@ -226,6 +231,7 @@ def test_70b_layer_decode_step_and_prefill_sampled(torch):
     got = U.from_device(x)
     want = O.run_layers(osh, wts, 0, 1, U.f64(xbits), O.OracleBatch(q_start, list(range(B)), befores), okv)
     err = U.rel_err(got, want)
+    U.assert_rms(got, want, U.RMS_BF16_FULLSIZE)
     assert err <= U.BF16_TOL, err
     # prefill: 4 requests of 2048 tokens in fresh slots
     for i in range(B):
@@ -247,4 +253,5 @@ def test_70b_layer_decode_step_and_prefill_sampled(torch):
         a, n = q_start[seq], 64
         want = O.run_layers(osh, wts, 0, 1, U.f64(xbits[a:a + n]), O.OracleBatch([0, n], [0], [0]), O.OracleKV())
         err = U.rel_err(got[a:a + n], want)
+        U.assert_rms(got[a:a + n], want, U.RMS_BF16_FULLSIZE)
         assert err <= U.BF16_TOL, (seq, err)

@@ -71,6 +71,7 @@ def test_tiny_prefill_then_decode_with_layer_streaming(torch, fp32):
     want2 = O.run_layers(os_, wts, 1, 2, want1, obatch, okv)
     err = U.rel_err(U.from_device(x), want2)
     assert err <= _tol(fp32), err
+    U.assert_rms(U.from_device(x), want2, U.RMS_FP32 if fp32 else U.RMS_BF16)
 
     # cache contents after prefill: K (rotated) and V of both layers
     for l in range(s.L):
@@ -229,6 +230,7 @@ def _mixed_case(torch, s, fp32, seqs):
     want = O.run_layers(os_, wts, 0, s.L, U.f64(xbits), O.OracleBatch(list(q_start), slots, befores), okv)
     got = U.from_device(x)
     inst.close()
+    U.assert_rms(got, want, U.RMS_FP32 if fp32 else U.RMS_BF16)
     return got, want, q_start
 
 

@@ -28,6 +28,7 @@ def test_rmsnorm(torch, fp32, T, H):
     want = O.rmsnorm(xr, gr, 1e-5)
     err = U.rel_err(U.from_device(y), want)
     assert err <= (U.FP32_TOL if fp32 else U.BF16_TOL), err
+    U.assert_rms(U.from_device(y), want, U.RMS_FP32 if fp32 else U.RMS_BF16_OP)
 
 
 def test_rmsnorm_constant_vector(torch):
@@ -87,6 +88,7 @@ def test_gemm(torch, fp32, mode, M, N, K):
     got = U.from_device(c)
     err = U.rel_err(got, want)
     assert err <= (U.FP32_TOL if fp32 else U.BF16_TOL), err
+    U.assert_rms(got, want, U.RMS_FP32 if fp32 else U.RMS_BF16_OP)
     if not fp32:
         # bf16 output rounding alone bounds the error far below the gate; a wrong tile would not
         assert U.mixed_err(got, want, 8e-3) <= 1.0
