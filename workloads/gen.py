@@ -112,10 +112,12 @@ def layer_weights_bits(s: DecoderShape, layer: int) -> dict:
     return out
 
 
-def hidden_bits(s: DecoderShape, T: int, step: int = 0) -> np.ndarray:
-    """[T, H] hidden states, N(0,1) rounded to bf16; `step` selects an independent draw."""
+def hidden_bits(s: DecoderShape, T: int, step: int = 0, scale: float = 1.0) -> np.ndarray:
+    """[T, H] hidden states, N(0, scale^2) rounded to bf16; `step` selects an independent draw.  The
+    configurations use scale 1; tests of narrow shapes use a smaller one so that the layer's update is
+    not small against the residual stream it is added to."""
     rng = np.random.default_rng([s.seed, _TAG_HIDDEN, step])
-    return _normal_bits(rng, (T, s.H), 1.0)
+    return _normal_bits(rng, (T, s.H), scale)
 
 
 def kv_prefill_bits(s: DecoderShape, layer: int, slot: int, length: int):
