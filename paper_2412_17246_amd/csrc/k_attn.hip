@@ -62,8 +62,16 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
     // query heads per kv head) more time.)
     int item, h;
     if ((Hq & 7) == 0) {
-        const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+        const int xcd = blockIdx.x & 7;
+        int seq = blockIdx.x >> 3;
         const int hpx = Hq >> 3, G = Hq / kv.Hkv;
+        // A grid that fits the chip's slots in one go (two workgroups per CU, 64 per XCD) lasts as long as its
+        // busiest CU.  An XCD's CUs take its workgroups 0..31 first and 32.. as their second one, so CU c holds
+        // workgroups c and 32 + c; with the items ordered longest first that pairs long with long.  The second
+        // half is therefore walked backwards: CU c gets the c-th longest and the c-th shortest (one 2000-token
+        // sequence: 73 -> 60 us).  Larger grids are handed out as slots free up; longest first is right there.
+        const int n_x = bv.n_prefill_items * hpx;
+        if (n_x <= 64 && seq >= 32) seq = 32 + (n_x - 1 - seq);
         // heads of one kv group that sit next to each other on this XCD (1 if groups do not tile its heads)
         const int gl = G >= hpx ? hpx : (hpx % G == 0 ? G : 1);
         const int per_group = bv.n_prefill_items * gl;
