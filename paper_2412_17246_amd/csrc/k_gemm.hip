@@ -1084,7 +1084,10 @@ static SkinnyPlan skinny_plan(int M, int N, int K, int mode) {
 #ifndef BZ_SK_MAX_M
 #define BZ_SK_MAX_M 256
 #endif
-static bool skinny_ok(int M, int N, int K) { return M >= 1 && M <= BZ_SK_MAX_M && K % kBK == 0 && N % 4 == 0; }
+static bool skinny_ok(int M, int N, int K) {
+    return M >= 1 && M <= BZ_SK_MAX_M && K % kBK == 0 && N % 4 == 0 &&
+           (uint64_t)2 * N * K < 0x7fffffffull;          // 32-bit byte offsets into the weights (2N rows in gate/up mode)
+}
 
 size_t gemm_workspace_bytes(int mode, int M, int N, int K) {
     if (skinny_ok(M, N, K)) return skinny_plan(M, N, K, mode).ws_bytes;
@@ -1093,8 +1096,7 @@ size_t gemm_workspace_bytes(int mode, int M, int N, int K) {
 }
 
 static bool skinny_applies(int mode, int M, int N, int K, const float* ws, size_t ws_bytes) {
-    return skinny_ok(M, N, K) && ws != nullptr && ws_bytes >= skinny_plan(M, N, K, mode).ws_bytes &&
-           (uint64_t)2 * N * K < 0x7fffffffull;
+    return skinny_ok(M, N, K) && ws != nullptr && ws_bytes >= skinny_plan(M, N, K, mode).ws_bytes;
 }
 
 struct SkinnyArgs {
