@@ -642,10 +642,12 @@ int bz_batch_create(const bz_batch_desc* d, bz_batch** out) {
     if (!d || d->n_seqs < 1 || !d->q_start || !d->seq_slot || !d->kv_len_before) return BZ_EINVAL;
     const int B = d->n_seqs;
     if (d->q_start[0] != 0) return BZ_EINVAL;
-    for (int s = 0; s < B; ++s) {
+    for (int s = 0; s < B; ++s)
         if (d->q_start[s + 1] < d->q_start[s] || d->kv_len_before[s] < 0 || d->seq_slot[s] < 0) return BZ_EINVAL;
-        for (int u = 0; u < s; ++u)
-            if (d->seq_slot[u] == d->seq_slot[s]) return BZ_EINVAL;
+    {   // every sequence in a slot of its own
+        std::vector<int32_t> sorted(d->seq_slot, d->seq_slot + B);
+        std::sort(sorted.begin(), sorted.end());
+        if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return BZ_EINVAL;
     }
     const int T = d->q_start[B];
     if (T < 1) return BZ_EINVAL;
