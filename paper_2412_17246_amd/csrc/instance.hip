@@ -322,7 +322,7 @@ int bz_destroy(bz_instance* I) {
     return BZ_OK;
 }
 
-int bz_create(const bz_config* cfg, bz_instance** out) {
+int bz_create(const bz_config* cfg, bz_instance** out) try {
     if (!out) return BZ_EINVAL;
     *out = nullptr;
     int rc = validate(cfg);
@@ -395,6 +395,10 @@ int bz_create(const bz_config* cfg, bz_instance** out) {
 #undef HIP_TRY_C
     *out = I;
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 int bz_sync(bz_instance* I) {
@@ -420,7 +424,7 @@ int bz_load_layer_from_device(bz_instance* I, int layer, const void* dev, size_t
     return enqueue_copy(I, layer, dev, n, hipMemcpyDeviceToDevice);
 }
 
-int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int n_shards) {
+int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int n_shards) try {
     if (!I || !shards || n_shards < 1 || n_shards > BZ_MAX_SHARDS) return BZ_EINVAL;
     if (layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
     // the shards must tile [0, layer_bytes) exactly: sort indices by offset, then walk
@@ -475,6 +479,10 @@ int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int
     I->stats.bytes_ingested += I->sz.layer_bytes;
     I->stats.layers_requested += 1;
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 int bz_unload_layer(bz_instance* I, int layer) {
@@ -636,7 +644,7 @@ int bz_batch_destroy(bz_batch* b) {
     return BZ_OK;
 }
 
-int bz_batch_create(const bz_batch_desc* d, bz_batch** out) {
+int bz_batch_create(const bz_batch_desc* d, bz_batch** out) try {
     if (!out) return BZ_EINVAL;
     *out = nullptr;
     if (!d || d->n_seqs < 1 || !d->q_start || !d->seq_slot || !d->kv_len_before) return BZ_EINVAL;
@@ -716,6 +724,10 @@ int bz_batch_create(const bz_batch_desc* d, bz_batch** out) {
     if (e != hipSuccess) { hip_fail(e, "hipMemcpy(batch)"); bz_batch_destroy(b); return BZ_EHIP; }
     *out = b;
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 int bz_batch_tokens(const bz_batch* b) { return b ? b->T : BZ_EINVAL; }
@@ -736,7 +748,7 @@ int bz_batch_advance(bz_instance* I, bz_batch* b) {
 
 // ---- execution ----------------------------------------------------------------------------
 
-int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hidden, int flags) {
+int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hidden, int flags) try {
     if (!I || !batch || !hidden) return BZ_EINVAL;
     if (a < 0 || b > I->sh.L || a > b) return BZ_EINVAL;
     if (batch->T > I->cfg.max_tokens) return BZ_ECAPACITY;
@@ -853,6 +865,10 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
     I->stats.tokens_run += (uint64_t)T * (uint64_t)(b - a);
     I->stats.layer_launches += (uint64_t)(b - a);
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 int bz_export_boundary(bz_instance* I, const void* hidden, size_t T, void* buf, int is_host) {

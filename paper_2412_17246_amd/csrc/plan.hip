@@ -1,5 +1,6 @@
 // Scale-plan generation: host code only (see blitz_plan.h for the model and the steps).
 #include <algorithm>
+#include <new>
 #include <set>
 #include <vector>
 
@@ -33,7 +34,7 @@ struct Chain {
 
 extern "C" int bz_plan_generate(const bz_plan_node* nodes, int n_nodes, int n_targets, double oversub, int n_layers,
                                 double layer_bytes, bz_plan_hop* hops, int max_hops, int* n_hops, int* n_chains,
-                                int* interferes) {
+                                int* interferes) try {
     if (!nodes || !hops || !n_hops || n_nodes < 1 || n_targets < 1 || n_layers < 1) return BZ_EINVAL;
     if (!(oversub >= 1.0) || !(layer_bytes > 0.0)) return BZ_EINVAL;
     std::vector<PNode> all((size_t)n_nodes);
@@ -138,4 +139,8 @@ extern "C" int bz_plan_generate(const bz_plan_node* nodes, int n_nodes, int n_ta
     if (n_chains) *n_chains = nc;
     if (interferes) *interferes = forced ? 1 : 0;
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }

@@ -7,6 +7,7 @@
 // driver (bz_zz_run), which polls the target's frontier and the two compute streams and issues
 // bz_run_layers / hand-offs accordingly.
 #include <chrono>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -80,7 +81,7 @@ struct bz_zz {
 extern "C" {
 
 int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, double source_free_at,
-                   int32_t* T_out, double* finish_out) {
+                   int32_t* T_out, double* finish_out) try {
     if (n_layers < 1 || n_requests < 1 || !T_out || !finish_out || load_time < 0 || source_free_at < 0) return BZ_EINVAL;
     if (policy != BZ_ZZ_ZIGZAG && policy != BZ_ZZ_BEST_EFFORT) return BZ_EINVAL;
     const int L = n_layers, N = n_requests;
@@ -147,9 +148,13 @@ int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, d
         finish_out[r] = fin[r];
     }
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
-int bz_zz_create(bz_instance* target, bz_instance* source, int policy, bz_zz** out) {
+int bz_zz_create(bz_instance* target, bz_instance* source, int policy, bz_zz** out) try {
     if (!out) return BZ_EINVAL;
     *out = nullptr;
     if (!target || !source || target == source) return BZ_EINVAL;
@@ -169,6 +174,10 @@ int bz_zz_create(bz_instance* target, bz_instance* source, int policy, bz_zz** o
     }
     *out = z;
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 int bz_zz_destroy(bz_zz* z) {
@@ -180,13 +189,17 @@ int bz_zz_destroy(bz_zz* z) {
     return BZ_OK;
 }
 
-int bz_zz_submit(bz_zz* z, const bz_batch* batch, void* hidden_target, void* hidden_source) {
+int bz_zz_submit(bz_zz* z, const bz_batch* batch, void* hidden_target, void* hidden_source) try {
     if (!z || !batch || !hidden_target || !hidden_source || hidden_target == hidden_source) return BZ_EINVAL;
     z->batch.push_back(batch);
     z->hid_t.push_back(hidden_target);
     z->hid_s.push_back(hidden_source);
     z->T.push_back(0);
     return (int)z->batch.size() - 1;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 // Hand-off of request r after `done` layers: copy the activation on the target's stream, then make
@@ -199,7 +212,7 @@ static int handoff(bz_zz* z, int r) {
     return BZ_OK;
 }
 
-int bz_zz_run(bz_zz* z) {
+int bz_zz_run(bz_zz* z) try {
     if (!z) return BZ_EINVAL;
     const int N = (int)z->batch.size();
     if (N == 0) return BZ_OK;
@@ -303,6 +316,10 @@ int bz_zz_run(bz_zz* z) {
     HIP_TRY(hipStreamSynchronize(tg->compute));
     HIP_TRY(hipStreamSynchronize(sr->compute));
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 int bz_zz_layers_on_target(const bz_zz* z, int request) {
