@@ -564,16 +564,20 @@ static int push_slot(bz_instance* I, int slot) {
     return BZ_OK;
 }
 
-int bz_kv_reserve(bz_instance* I, int slot, int capacity_tokens) {
+int bz_kv_reserve(bz_instance* I, int slot, int capacity_tokens) try {
     if (!I || slot < 0 || slot >= I->cfg.max_seqs || capacity_tokens < 1) return BZ_EINVAL;
     if (capacity_tokens > I->cfg.max_seq_len) return BZ_ECAPACITY;
     if (I->slots->reserved(slot)) return BZ_EBUSY;
     // the K cache is stored in blocks of 32 positions
     if (!I->slots->reserve(slot, ((int64_t)capacity_tokens + 31) / 32 * 32)) return BZ_ECAPACITY;
     return push_slot(I, slot);
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
-int bz_kv_release(bz_instance* I, int slot) {
+int bz_kv_release(bz_instance* I, int slot) try {
     if (!I || slot < 0 || slot >= I->cfg.max_seqs) return BZ_EINVAL;
     if (!I->slots->reserved(slot)) return BZ_ESTATE;
     if (!I->dry) {
@@ -582,6 +586,10 @@ int bz_kv_release(bz_instance* I, int slot) {
     }
     I->slots->release(slot);
     return push_slot(I, slot);
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 int64_t bz_kv_free_tokens(bz_instance* I) {
@@ -902,14 +910,18 @@ int bz_stats_read(bz_instance* I, bz_stats* out) {
     return BZ_OK;
 }
 
-int bz_profile_enable(bz_instance* I, int on) {
+int bz_profile_enable(bz_instance* I, int on) try {
     if (!I) return BZ_EINVAL;
     if (I->dry) return BZ_ESTATE;
     I->prof_on = on != 0;
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
-int bz_profile_read(bz_instance* I, bz_profile* out) {
+int bz_profile_read(bz_instance* I, bz_profile* out) try {
     if (!I || !out) return BZ_EINVAL;
     if (I->dry) return BZ_ESTATE;
     memset(out, 0, sizeof *out);
@@ -926,6 +938,10 @@ int bz_profile_read(bz_instance* I, bz_profile* out) {
     }
     I->prof.clear();
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
 }
 
 // ---- single operations -----------------------------------------------------------------------
