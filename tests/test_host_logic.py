@@ -121,6 +121,49 @@ def test_kv_slot_bookkeeping(dry):
     assert _status(dry.kv_reserve, 4, 10) == "BZ_EINVAL"
 
 
+def test_kv_slot_allocator_against_a_model_on_random_sequences(lib):
+    """Random reserve / release sequences on a dry-run instance against a few lines of Python that keep
+    the set of occupied runs: first fit, requests rounded up to 32 positions, free runs merged."""
+    rng = np.random.default_rng(11)
+    for trial in range(20):
+        n_slots = int(rng.integers(2, 24))
+        total = int(rng.integers(4, 80)) * 32
+        inst = B.Instance(workloads.CONFIGS["tiny"], max_seqs=n_slots, max_seq_len=total, max_tokens=8, kv_tokens=total,
+                          dry_run=True, fp32_debug=bool(lib.bz_build_info() & 1))
+        held = {}                                            # slot -> (offset, length)
+
+        def free_runs():
+            runs, at = [], 0
+            for off, ln in sorted(held.values()):
+                if off > at:
+                    runs.append((at, off - at))
+                at = off + ln
+            if at < total:
+                runs.append((at, total - at))
+            return runs
+
+        for step in range(200):
+            slot = int(rng.integers(0, n_slots))
+            if slot in held and rng.random() < 0.6:
+                inst.kv_release(slot)
+                del held[slot]
+            else:
+                want = int(rng.integers(1, total // 2 + 2))
+                need = (want + 31) // 32 * 32
+                got = _status(inst.kv_reserve, slot, want)
+                if slot in held:
+                    assert got == "BZ_EBUSY"
+                else:
+                    fit = next(((off, ln) for off, ln in free_runs() if ln >= need), None)
+                    if want > total or fit is None:
+                        assert got == "BZ_ECAPACITY", (trial, step, want, free_runs())
+                    else:
+                        assert got == "BZ_OK", (trial, step, want, free_runs())
+                        held[slot] = (fit[0], need)
+            assert inst.kv_free_tokens() == max([ln for _, ln in free_runs()], default=0)
+        inst.close()
+
+
 def test_frontier_and_argument_checks_without_a_gpu(dry):
     assert dry.frontier() == 0
     assert dry.layer_ready(0) is False
