@@ -502,3 +502,57 @@ def test_decode_batch_of_300_sequences_with_advance(torch):
                             O.OracleBatch(list(range(B + 1)), list(range(B)), [n + step for n in lens]), okv)
         assert U.rel_err(U.from_device(x), want) <= U.BF16_TOL, step
     inst.close()
+
+
+def test_slots_reused_out_of_order_and_sequences_in_any_slot_order(torch):
+    """Slots released and reserved again land in holes of the arena, and a batch may name its slots in any
+    order: sequence s of the batch lives where seq_slot[s] says, not at position s."""
+    s = MIX
+    os_ = U.oracle_shape(s)
+    inst = U.make_instance(s, max_seqs=6, max_seq_len=400, max_tokens=256, kv_tokens=96 + 64 + 160 + 128)
+    bits = {l: W.layer_weights_bits(s, l) for l in range(s.L)}
+    wts = {l: U.oracle_weights(bits[l]) for l in range(s.L)}
+    U.load_all_layers(inst, s)
+    inst.kv_reserve(0, 96)
+    inst.kv_reserve(1, 64)
+    inst.kv_reserve(2, 160)
+    inst.kv_release(1)
+    inst.kv_reserve(5, 40)                      # into the hole slot 1 left (40 rounds up to its 64 positions)
+    inst.kv_reserve(1, 128)                     # behind everything else
+    assert inst.kv_free_tokens() == 0           # 96 + 64 + 160 + 128 positions, all taken
+    # (new tokens, cached before) per sequence, and the slot each one lives in
+    seqs = [(30, 0), (1, 95), (50, 60), (1, 127), (7, 20)]
+    slots = [5, 0, 2, 1, 3]
+    inst.kv_release(5)
+    inst.kv_reserve(3, 27)                      # 32 positions at the start of the hole
+    inst.kv_reserve(5, 30)                      # the other 32
+    okv = O.OracleKV()
+    for (n, before), slot in zip(seqs, slots):
+        for l in range(s.L):
+            if before:
+                kb, vb = W.kv_prefill_bits(s, l, slot, before)
+                okv.put(l, slot, U.f64(kb), U.f64(vb))
+                inst.kv_write(l, slot, 0, before, kb, vb)
+    q_start = np.concatenate([[0], np.cumsum([n for n, _ in seqs])])
+    befores = [b for _, b in seqs]
+    T = int(q_start[-1])
+    xbits = W.hidden_bits(s, T, step=9, scale=1.0 / 16)
+    x = U.to_device(xbits, False)
+    torch.cuda.synchronize()
+    inst.run_layers(0, s.L, inst.batch(q_start, slots, befores), x)
+    inst.sync()
+    got = U.from_device(x)
+    want = O.run_layers(os_, wts, 0, s.L, U.f64(xbits), O.OracleBatch(list(q_start), slots, befores), okv)
+    for i in range(len(seqs)):
+        a, b = q_start[i], q_start[i + 1]
+        assert U.rel_err(got[a:b], want[a:b]) <= U.BF16_TOL, (i, seqs[i], slots[i])
+    U.assert_rms(got, want, U.RMS_BF16)
+    # what the layers appended went to the right slots: read back sequence 4's cache (slot 3) in layer 1
+    n, before = seqs[4]
+    kk = torch.empty(before + n, s.Hkv, s.d, dtype=torch.bfloat16, device="cuda")
+    vv = torch.empty_like(kk)
+    inst.kv_read(1, 3, 0, before + n, kk, vv)
+    inst.sync()
+    assert U.rel_err(U.from_device(kk), okv.store[(1, 3)][0]) <= U.BF16_TOL
+    assert U.rel_err(U.from_device(vv), okv.store[(1, 3)][1]) <= U.BF16_TOL
+    inst.close()
