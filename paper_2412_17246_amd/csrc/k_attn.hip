@@ -159,19 +159,38 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
             const bf16* Ks = smem + (tile & 1) * STAGE;
             const bf16* Vs = Ks + 2 * BLK;
             f32x16 sacc[2];
-            // the next tile's loads go out one by one between the score MFMAs: a load holds the wave's
-            // instruction stream for tens of cycles, which an MFMA in flight covers
+            // Operand fetch runs ahead of the MFMAs by hand: written as "read, multiply" the compiler waits for
+            // every LDS read right before its MFMA, and the score phase takes 2.6 times its 16 MFMAs.  Here the
+            // eight K fragments of the first key block are requested together; each is replaced by the second
+            // block's fragment as soon as its MFMA has gone, and under the second block's MFMAs the V fragments
+            // of the first two k-steps of P.V are requested.
+            // The next tile's loads go out one by one between the score MFMAs: a load holds the wave's
+            // instruction stream for tens of cycles, which an MFMA in flight covers.
             constexpr int EVERY = (2 * KS) / (2 * NL);
+            auto k_frag = [&](int kb, int ks) {
+                return *reinterpret_cast<const bf16x8*>(&Ks[kb * BLK + ((ks * 2 + lh) * 32 + lq) * 8]);
+            };
+            auto v_frag = [&](int t, int b) {
+                return *reinterpret_cast<const bf16x8*>(&Vs[(t >> 1) * BLK + ((2 * (t & 1) + lh) * D + b * 32 + lq) * 8]);
+            };
+            bf16x8 ka[KS], vfr[2][DB];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) ka[ks] = k_frag(0, ks);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+            __builtin_amdgcn_sched_barrier(0);             // the order below is the order wanted: nothing is moved across
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-#pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[kb * BLK + ((ks * 2 + lh) * 32 + lq) * 8]);
-                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
+                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[ks], sacc[kb], 0, 0, 0);
+                    if (kb == 0) ka[ks] = k_frag(1, ks);
+                    else if (ks < 2 * DB) vfr[ks / DB][ks % DB] = v_frag(ks / DB, ks % DB);
                     const int m = kb * KS + ks;
                     if (m % EVERY == EVERY - 1) issue_one(nxt, (tile + 1) & 1, m / EVERY);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (kbase + BK - 1 > wave_min_pos) {             // wave-uniform: the diagonal crosses this tile
@@ -217,9 +236,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const bf16* __rest
                 for (int e = 0; e < 8; ++e) pf[e] = (bf16)sacc[t >> 1][8 * (t & 1) + e];
 #pragma unroll
                 for (int b = 0; b < DB; ++b) {
-                    const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
-                        &Vs[(t >> 1) * BLK + ((2 * (t & 1) + lh) * D + b * 32 + lq) * 8]);
-                    o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[b], 0, 0, 0);
+                    o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[t & 1][b], pf, o[b], 0, 0, 0);
+                    if (t + 2 < 4) vfr[t & 1][b] = v_frag(t + 2, b);
                 }
             }
         }
