@@ -350,6 +350,19 @@ size_t bz_op_gemm_workspace_bytes(int mode, int M, int N, int K);
 int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K, void* workspace,
                size_t workspace_bytes, void* stream);
 
+/* bz_op_gemm for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels,
+ * schedules and results (bit for bit) as bz_op_gemm called with a sufficient workspace; the scratch comes
+ * from a static device array of BZ_STATIC_SCRATCH_BYTES that each GPU the library runs on holds until
+ * the process ends.  The call allocates and frees nothing.  BZ_ECAPACITY, before any GPU work, if
+ * bz_op_gemm_workspace_bytes(mode, M, N, K) exceeds BZ_STATIC_SCRATCH_BYTES (a problem of up to 256
+ * rows whose split-K partial sums are larger; every larger problem fits).  All calls on one GPU share
+ * the one array: calls that overlap in time on the same GPU (two streams, two threads) race; issue
+ * them on one stream or order them with events.  Nothing in the array has to be cleared between calls. */
+#define BZ_STATIC_SCRATCH_BYTES (64u << 20)
+int bz_op_gemm_static(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K,
+                      void* stream);
+
 #ifdef __cplusplus
 }
 #endif

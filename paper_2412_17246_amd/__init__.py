@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     load_library,
     make_config,
     op_gemm,
+    op_gemm_static,
     op_gemm_workspace_bytes,
     op_rmsnorm,
     plan_generate,

@@ -152,6 +152,7 @@ SIGNATURES = {
     "bz_op_rmsnorm": (C.c_int, [_P, _P, _P, C.c_int, C.c_int, C.c_float, _P]),
     "bz_op_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int]),
     "bz_op_gemm": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P, C.c_size_t, _P]),
+    "bz_op_gemm_static": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, _P]),
 }
 
 _libs: Dict[str, C.CDLL] = {}
@@ -516,3 +517,14 @@ def op_gemm(mode: int, a, w, r, c, M: int, N: int, K: int, stream=None, fp32_deb
                         stream.cuda_stream if stream else 0)
     if rc:
         raise BzError(rc, "bz_op_gemm")
+
+
+BZ_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def op_gemm_static(mode: int, a, w, r, c, M: int, N: int, K: int, stream=None, fp32_debug: bool = False) -> None:
+    """bz_op_gemm with the library's static scratch: allocates nothing."""
+    lib = load_library(fp32_debug)
+    rc = lib.bz_op_gemm_static(mode, _ptr(a), _ptr(w), _ptr(r), _ptr(c), M, N, K, stream.cuda_stream if stream else 0)
+    if rc:
+        raise BzError(rc, "bz_op_gemm_static", lib.bz_last_hip_error().decode() if rc == -6 else "")

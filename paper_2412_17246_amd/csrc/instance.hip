@@ -969,4 +969,52 @@ int bz_op_gemm(int mode, const void* a, const void* w, const void* r, void* c, i
     return BZ_OK;
 }
 
+// ---- bz_op_gemm for callers that cannot allocate ----------------------------------------------
+// Same kernels and schedules as bz_op_gemm; the scratch the schedules need (split-K partial sums,
+// partial tiles) lives in a file-scope device array instead of a caller's workspace.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the address that kernels and copies use is
+// looked up once per device, with that device current, and kept.
+
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[BZ_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+std::atomic<void*> g_scratch_ptr[64];        // per device ordinal; nullptr until looked up
+
+int static_scratch_of_current_device(void** out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return BZ_EINVAL;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return BZ_EHIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // racing threads store the same address
+    }
+    *out = p;
+    return BZ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bz_op_gemm_static(int mode, const void* a, const void* w, const void* r, void* c, int M, int N, int K,
+                      void* stream) {
+    if (mode < 0 || mode > 2 || !a || !w || !c || (mode == 1 && !r)) return BZ_EINVAL;
+    if (M < 0 || N < 1 || K < 8 || K % 8) return BZ_EINVAL;
+    const size_t need = gemm_workspace_bytes(mode, M, N, K);
+    if (need > (size_t)BZ_STATIC_SCRATCH_BYTES) return BZ_ECAPACITY;      // before anything touches the GPU
+    void* ws = nullptr;
+    int rc = static_scratch_of_current_device(&ws);
+    if (rc) return rc;
+    // nothing in the scratch has to start at zero: every schedule writes each partial sum it later reads
+    launch_gemm(mode, (const act_t*)a, (const bf16*)w, (const act_t*)r, (act_t*)c, M, N, K, (float*)ws,
+                (size_t)BZ_STATIC_SCRATCH_BYTES, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return BZ_OK;
+}
+
 }  // extern "C"
