@@ -1,26 +1,30 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-Default workload `prefill_stream` (the configuration the headline metric is quoted on): a
-Llama-2-7B-shaped decoder (32 layers) whose weights start in pinned host memory.  One step = scale
-start to first token: every layer is requested with load_layer (chunked host->HBM copies on the
-copy stream) and, at the same moment, one packed prefill batch of 8 requests (lognormal lengths)
-is sent through run_layers(0, L), each layer gated on its own ingest event, so resident layers
-execute while later ones are still arriving.  Hidden states, KV cache and workspaces are resident
-in HBM before the timed region; the weights' trip over the host link is the method's own ingest
-step and is inside it.  The all-resident rate of the same batch is reported beside it.
+Default (`--workload all`, what the round driver runs): ONE JSON line whose headline is the largest
+single-GPU configuration, with the other configurations as extra keys of the same line.
 
-Other workloads (`--workload`), used for the design notes and profiles, not by the round driver:
-  decode       8B-GQA-shaped, 64 sequences with caches of length uniform[256,4096]; a step is one
-               decode step through all layers; `--split k` hands the activation from an instance
-               running [0,k) to one running [k,L) every step and checks bit-equality first
-  mixed_ttft   13B-shaped, layers [0,20) resident, [20,40) ingested from t0 while one mixed batch
-               (16 prefill + 48 decode sequences) runs behind the frontier
-  `--shape 70b --requests 4 --fixed-len 2048 --distinct-blobs 4` gives the 70B-shaped streamed
-  prefill (layer i is fed from pinned blob i mod 4: byte counts and shapes are real, the host
-  copy is smaller than 137 GB).
+  headline  70B-shaped decoder (80 layers, 136.9 GB of weights) streamed from pinned host memory behind a
+            4 x 2048-token prefill batch.  One step = scale start to first token: every layer is requested
+            with load_layer (chunked host->HBM copies on the copy stream) and, at the same moment, the packed
+            batch is sent through run_layers(0, L), each layer gated on its own ingest event, so resident
+            layers execute while later ones are still arriving.  Hidden states, KV cache and workspaces are
+            resident in HBM before the timed region; the weights' trip over the host link is the method's own
+            ingest step and is inside it.  Layer i is fed from pinned blob i mod 4 (the host copy of all 80
+            would be 137 GB): byte counts and shapes are real.  `--steps` / `--warmup` apply to this leg.
+  configs.cfg5_70b_decode      the same instance, all layers now resident: 256 decode steps of 32 sequences
+                               with caches uniform[512,4096]
+  configs.cfg2_7b_prefill_stream   7B-shaped, 32 layers streamed behind an 8-request prefill batch (6768 tokens)
+  configs.cfg3_8b_gqa_decode   8B-GQA-shaped, 64 sequences, caches uniform[256,4096], 128 decode steps, with a
+                               live split at layer 16 (two instance handles) checked bit for bit first
+  configs.cfg4_13b_mixed_ttft  13B-shaped, layers [0,20) resident, [20,40) ingested from t0 behind one mixed
+                               batch (16 prefill requests + 48 decode sequences): TTFT, overlap efficiency
 
-Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU by construction.
+Single legs (`--workload prefill_stream | decode | mixed_ttft | zigzag`) are what the profiles under
+profiles/ were taken with; see each file for its command.
+
+Prints ONE JSON line on stdout (progress goes to stderr).  `--gpus N` with N > 1 is refused: this build is
+single-GPU by construction.
 """
 from __future__ import annotations
 
@@ -40,14 +44,20 @@ import workloads as W  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0
-# Bytes moved per launch of the dominant kernel of the default workload (gate/up projection, M = 6768):
-# rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE of this script, scaled by what the same counters read for
-# a 1 GiB device copy (x2.0 and x1.0); see profiles/gemm_big_kernel_7b_prefill_stream.txt.  L2-miss traffic
-# summed over the 8 XCD L2s, mostly served by the Infinity Cache.
-# The gate/up figure covers the three launches of that projection (whole tiles, split last-round tiles,
-# their fix-up); the decode-attention figure covers the split-KV kernel and the combine.
-MEASURED_TRAFFIC = {("7b", 32, 6768, "gemm_gateup"): 1.881e9 + 0.150e9 + 0.069e9 + 0.061e9 + 0.061e9,
-                    ("8b_gqa", 32, 64, "attn_decode"): 0.5671e9 + 0.0114e9}
+# HBM-side traffic per launch of a dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script, each scaled by what the same counter reads for a device copy of known size.  Keyed by (shape, rows,
+# kernel class); the value names the summary under profiles/ that holds the counters and the command.  A
+# workload without an entry reports "traffic": null.  The algorithmic bytes are computed, not looked up.
+MEASURED_TRAFFIC = {}
+
+
+def traffic_of(shape_name, rows, kernel):
+    hit = MEASURED_TRAFFIC.get((shape_name, rows, kernel))
+    return (hit[0], hit[1]) if hit else (None, None)
+
+
+def note(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
 # ------------------------------------------------------------------------------- helpers
@@ -175,22 +185,130 @@ def base_record(metric, value, unit, args, ms_per_step, workload, extra_cfg):
             "dtype": "bf16", "data": "synthetic", "config": cfg}
 
 
-def gemm_roofline(prof):
+def gemm_roofline(prof, shape_name, rows):
+    """Roofline record of the GEMM class with the largest summed time, from the library's own HIP events on
+    the compute stream (bz_profile_*), plus the rate over all GEMM classes."""
     classes = [k for k in prof if k.startswith("gemm") and prof[k]["launches"]]
     dom = max(classes, key=lambda k: prof[k]["ms"])
     d = prof[dom]
     achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
     allf = sum(prof[k]["flops"] for k in classes)
     allms = sum(prof[k]["ms"] for k in classes)
+    traffic, source = traffic_of(shape_name, rows, dom)
+    per_class = {k: prof[k]["flops"] / (prof[k]["ms"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS for k in classes}
     return ({"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-             "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "launches": d["launches"],
-             "avg_ms": d["ms"] / d["launches"]},
+             "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_profile": source,
+             "algorithmic_bytes": d["bytes"] / d["launches"], "algorithmic_flops": d["flops"] / d["launches"],
+             "launches": d["launches"], "avg_ms": d["ms"] / d["launches"], "frac_by_class": per_class},
             allf / (allms * 1e-3) / 1e12)
+
+
+def decode_leg(inst, torch, shape, batch, xs, n_steps, steps, warmup, start, B):
+    """Timed decode steps on a resident instance: `steps` steps with the library's per-kernel events (for the
+    roofline record), then the same number without them (the reported rate)."""
+    for st in range(start, start + warmup):
+        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
+        inst.batch_advance(batch)
+    inst.sync()
+    inst.profile_enable(True)
+    inst.profile_read()
+    t0 = time.perf_counter()
+    for st in range(start + warmup, start + warmup + steps):
+        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
+        inst.batch_advance(batch)
+    inst.sync()
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t0
+    prof = inst.profile_read()
+    inst.profile_enable(False)
+    t0 = time.perf_counter()
+    for st in range(steps):
+        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
+        inst.batch_advance(batch)
+    inst.sync()
+    plain = time.perf_counter() - t0
+    d = prof["attn_decode"]
+    achieved = d["bytes"] / (d["ms"] * 1e-3) / 1e9
+    traffic, source = traffic_of(shape.name, B, "attn_decode")
+    weights_gb = shape.L * inst.layer_bytes / 1e9
+    kv_gb = d["bytes"] / steps / 1e9
+    return {
+        "decode_tokens_per_s": B * steps / plain,
+        "ms_per_step": plain / steps * 1e3,
+        "steps": steps,
+        "ms_per_step_with_profiling_events": total / steps * 1e3,
+        "weights_GB_per_step": weights_gb,
+        "kv_GB_per_step": kv_gb,
+        "hbm_roofline_frac_whole_step": (weights_gb + kv_gb) / (plain / steps) / PEAK_HBM_GBPS,
+        "kernel_ms_per_step": {k: v["ms"] / steps for k, v in prof.items() if v["launches"]},
+        "roofline": {"bound": "hbm", "kernel": "attn_decode", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic, "traffic_profile": source,
+                     "algorithmic_bytes": d["bytes"] / d["launches"], "launches": d["launches"],
+                     "avg_ms": d["ms"] / d["launches"]},
+    }
+
+
+def live_split_check(torch, make_instance, shape, blobs, lens, kv_seed, xs, k, steps, whole=None, whole_batch=None):
+    """Cooperative execution at the real shape: a target instance holding layers [0,k) and a source instance
+    holding [k,L), each with the caches of its own layers, against one instance holding everything.  Every
+    step hands the activation over at the boundary and advances the caches by one position.  Returns the list
+    of per-step bit-equality flags.  `whole` / `whole_batch`: an existing fully loaded instance (with caches
+    filled from the same `kv_seed`) and its batch; created here when absent."""
+    B = len(lens)
+    own_whole = whole is None
+    insts = [make_instance(), make_instance()] + ([make_instance()] if own_whole else [])
+    tgt, src = insts[0], insts[1]
+    if own_whole:
+        whole = insts[2]
+    for l in range(shape.L):
+        (tgt if l < k else src).load_layer_from_device(l, blobs[l])
+        if own_whole:
+            whole.load_layer_from_device(l, blobs[l])
+    for inst in insts:
+        inst.sync()
+    gen_kv = torch.Generator(device="cuda")
+    gen_kv.manual_seed(kv_seed)
+    for i, n in enumerate(lens):
+        for l in range(shape.L):
+            kk = torch.randn(int(n), shape.Hkv, shape.d, generator=gen_kv, device="cuda").to(torch.bfloat16)
+            vv = torch.randn(int(n), shape.Hkv, shape.d, generator=gen_kv, device="cuda").to(torch.bfloat16)
+            torch.cuda.synchronize()
+            (tgt if l < k else src).kv_write(l, i, 0, int(n), kk, vv)
+            if own_whole:
+                whole.kv_write(l, i, 0, int(n), kk, vv)
+    for inst in insts:
+        inst.sync()
+    if whole_batch is None:
+        whole_batch = whole.batch(list(range(B + 1)), list(range(B)), [int(n) for n in lens])
+    batch2 = tgt.batch(list(range(B + 1)), list(range(B)), [int(n) for n in lens])
+    buf = torch.empty(B, shape.H, dtype=torch.bfloat16, device="cuda")
+    flags = []
+    for st in range(steps):
+        a = xs[st].clone()
+        b = xs[st].clone()
+        c = torch.empty_like(b)
+        torch.cuda.synchronize()
+        whole.run_layers(0, shape.L, whole_batch, a)
+        whole.batch_advance(whole_batch)
+        tgt.run_layers(0, k, batch2, b)
+        tgt.export_boundary(b, B, buf)
+        src.import_boundary(c, B, buf)            # the instances share one compute stream: ordered
+        src.run_layers(k, shape.L, batch2, c)
+        src.batch_advance(batch2)
+        whole.sync()
+        src.sync()
+        flags.append(bool(torch.equal(a.view(torch.int16), c.view(torch.int16))))
+    for inst in insts:
+        inst.close()
+    return flags
 
 
 # ------------------------------------------------------------------------------- workloads
 
-def run_prefill_stream(args, torch, Instance):
+def run_prefill_stream(args, torch, Instance, then_decode=None):
+    """Streamed prefill leg.  `then_decode` = dict(B, lo, hi, steps, warmup): afterwards, with every layer
+    resident, the same instance serves that many decode steps of B sequences with caches uniform[lo, hi];
+    the function then returns (prefill record, decode record)."""
     base = W.CONFIGS[args.shape]
     shape = with_layers(base, args.layers)
     if args.fixed_len:
@@ -199,15 +317,23 @@ def run_prefill_stream(args, torch, Instance):
         lens = W.lognormal_lengths(shape.seed, args.requests, 512.0, 0.6, 16, 2048)
     q_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     T, B = int(q_start[-1]), len(lens)
+    max_seqs, max_len, kv_tokens = B, int(lens.max()) + 1, int(lens.sum()) + 32 * B
+    if then_decode:
+        dB, d_steps_total = then_decode["B"], 2 * then_decode["steps"] + then_decode["warmup"] + 4
+        d_lens = W.uniform_lengths(base.seed, dB, then_decode["lo"], then_decode["hi"])
+        max_seqs = max(B, dB)
+        max_len = max(max_len, then_decode["hi"] + d_steps_total + 8)
+        kv_tokens = max(kv_tokens, int(d_lens.sum()) + dB * (d_steps_total + 40))
     stream = torch.cuda.Stream()
-    inst = Instance(shape, max_seqs=B, max_seq_len=int(lens.max()) + 1, max_tokens=T,
-                    kv_tokens=int(lens.sum()) + 32 * B, chunk_bytes=args.chunk_mib << 20, compute_stream=stream)
+    inst = Instance(shape, max_seqs=max_seqs, max_seq_len=max_len, max_tokens=T,
+                    kv_tokens=kv_tokens, chunk_bytes=args.chunk_mib << 20, compute_stream=stream)
     for i, n in enumerate(lens):
         inst.kv_reserve(i, int(n))
     gen = torch.Generator(device="cuda")
     gen.manual_seed(shape.seed)
     n_blobs = min(shape.L, args.distinct_blobs) if args.distinct_blobs else shape.L
     blobs = [gen_layer_blob_gpu(torch, inst, shape, gen) for _ in range(n_blobs)]
+    note(f"{shape.name}: instance and {n_blobs} pinned layer blobs ready ({inst.layer_bytes / 1e6:.0f} MB each)")
     shard_views = []
     if args.shards > 1:
         step = -(-inst.layer_bytes // args.shards // 256) * 256
@@ -238,10 +364,11 @@ def run_prefill_stream(args, torch, Instance):
         one_step()
         inst.sync()
     n_streams = pick_ingest_streams(args, inst, reset, one_step, torch)
+    note(f"{shape.name}: warm-up done, {n_streams} copy stream(s); timing {args.steps} steps")
     inst.profile_enable(True)
     inst.profile_read()
     total, ingest_ms = 0.0, []
-    for _ in range(args.steps):           # resets are outside the clock
+    for i in range(args.steps):           # resets are outside the clock
         reset()
         t0 = time.perf_counter()
         one_step()
@@ -249,6 +376,8 @@ def run_prefill_stream(args, torch, Instance):
         torch.cuda.synchronize()
         total += time.perf_counter() - t0
         ingest_ms.append(inst.layer_ready_ms(shape.L - 1))
+        if total > 20.0 * (1 + i // 8):
+            note(f"{shape.name}: step {i + 1}/{args.steps}")
     prof = inst.profile_read()
     inst.profile_enable(False)
     ms_per_step = total / args.steps * 1e3
@@ -261,8 +390,7 @@ def run_prefill_stream(args, torch, Instance):
     inst.sync()
     resident_s = (time.perf_counter() - t0) / 3
 
-    roof, all_tf = gemm_roofline(prof)
-    roof["traffic"] = MEASURED_TRAFFIC.get((shape.name, shape.L, T, roof["kernel"]))
+    roof, all_tf = gemm_roofline(prof, shape.name, T)
     out = base_record("prefill tokens/s on partially loaded model", T * args.steps / total, "tokens/s", args,
                       ms_per_step,
                       f"{shape.name}-shaped decoder, {shape.L} layers streamed from pinned host memory while a packed "
@@ -273,16 +401,36 @@ def run_prefill_stream(args, torch, Instance):
     out.update({
         "ttft_ms": ms_per_step,
         "ingest_GBps": shape.L * inst.layer_bytes / (float(np.median(ingest_ms)) * 1e-3) / 1e9,
+        "ingested_GB_per_step": shape.L * inst.layer_bytes / 1e9,
         "resident_prefill_tokens_per_s": T / resident_s,
         "resident_ms": resident_s * 1e3,
         "gemm_TFLOPs_all_classes": all_tf,
         "kernel_ms_per_step": {k: v["ms"] / args.steps for k, v in prof.items() if v["launches"]},
         "roofline": roof,
     })
+    dec = None
+    if then_decode:
+        # every layer is resident now; the prefill batch's slots go, the decode sequences' come
+        for i in range(B):
+            inst.kv_release(i)
+        for i, n in enumerate(d_lens):
+            inst.kv_reserve(i, int(n) + d_steps_total + 8)
+        gen_kv = torch.Generator(device="cuda")
+        gen_kv.manual_seed(base.seed + 100)
+        for i, n in enumerate(d_lens):
+            fill_kv(torch, inst, shape, gen_kv, i, int(n))
+        note(f"{shape.name}: caches of {dB} decode sequences filled; {then_decode['steps']} decode steps")
+        xs = torch.randn(d_steps_total, dB, shape.H, generator=gen, device="cuda").to(torch.bfloat16)
+        dbatch = inst.batch(list(range(dB + 1)), list(range(dB)), [int(n) for n in d_lens])
+        torch.cuda.synchronize()
+        dec = decode_leg(inst, torch, shape, dbatch, xs, d_steps_total, then_decode["steps"], then_decode["warmup"], 0, dB)
+        dec["workload"] = (f"{shape.name}-shaped decoder, {shape.L} layers resident, continuous decode of {dB} sequences "
+                           f"with cache lengths uniform[{then_decode['lo']},{then_decode['hi']}]")
+        dec["mean_cache_len"] = float(d_lens.mean())
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_prefill(base)
     inst.close()
-    return out
+    return (out, dec) if then_decode else out
 
 
 def run_decode(args, torch, Instance):
@@ -294,7 +442,8 @@ def run_decode(args, torch, Instance):
     if args.fixed_len:                    # every cache the same length (no short sequences, no ragged last chunks)
         lens = np.full(B, args.fixed_len, dtype=np.int64)
         lo = hi = args.fixed_len
-    n_steps = 2 * args.steps + args.warmup + 4     # every step appends a position: profiled steps, then the timed ones
+    n_split_steps = 8 if args.split else 0
+    n_steps = 2 * args.steps + args.warmup + 4 + n_split_steps     # every step appends a position
     stream = torch.cuda.Stream()
     gen = torch.Generator(device="cuda")
     gen.manual_seed(base.seed)
@@ -322,96 +471,32 @@ def run_decode(args, torch, Instance):
     gen_kv.manual_seed(base.seed + 100)
     for i, n in enumerate(lens):
         fill_kv(torch, inst, shape, gen_kv, i, int(n))
+    note(f"{shape.name}: {shape.L} layers resident, caches of {B} sequences filled")
     xs = torch.randn(n_steps, B, shape.H, generator=gen, device="cuda").to(torch.bfloat16)
     batch = inst.batch(list(range(B + 1)), list(range(B)), [int(n) for n in lens])
     torch.cuda.synchronize()
 
     split_note = None
-    start = 0
     if args.split:
-        # live split (cooperative execution): the target instance runs layers [0,k) with its own caches,
-        # hands the activation over, the source instance runs [k,L) with its own; outputs are compared
-        # bit for bit with the unsplit instance over 4 steps
-        k = args.split
-        tgt, src = make_instance(), make_instance()
-        for l in range(shape.L):
-            (tgt if l < k else src).load_layer_from_device(l, blobs[l])
-        tgt.sync()
-        src.sync()
-        gen_kv.manual_seed(base.seed + 100)
-        for i, n in enumerate(lens):
-            for l in range(shape.L):
-                kk = torch.randn(int(n), shape.Hkv, shape.d, generator=gen_kv, device="cuda").to(torch.bfloat16)
-                vv = torch.randn(int(n), shape.Hkv, shape.d, generator=gen_kv, device="cuda").to(torch.bfloat16)
-                torch.cuda.synchronize()
-                (tgt if l < k else src).kv_write(l, i, 0, int(n), kk, vv)
-        tgt.sync()
-        src.sync()
-        batch2 = tgt.batch(list(range(B + 1)), list(range(B)), [int(n) for n in lens])
-        buf = torch.empty(B, shape.H, dtype=torch.bfloat16, device="cuda")
-        ok = True
-        for st in range(4):
-            a = xs[st].clone()
-            b = xs[st].clone()
-            c = torch.empty_like(b)
-            torch.cuda.synchronize()
-            inst.run_layers(0, shape.L, batch, a)
-            inst.batch_advance(batch)
-            tgt.run_layers(0, k, batch2, b)
-            tgt.export_boundary(b, B, buf)
-            src.import_boundary(c, B, buf)        # both instances share the compute stream: ordered
-            src.run_layers(k, shape.L, batch2, c)
-            src.batch_advance(batch2)
-            inst.sync()
-            src.sync()
-            ok = ok and torch.equal(a.view(torch.int16), c.view(torch.int16))
-        split_note = {"split_layer": k, "bit_exact_steps": 4, "bit_exact": bool(ok)}
-        tgt.close()
-        src.close()
-        if not ok:
+        # live split (cooperative execution) against this instance, bit for bit, over steps that take at least
+        # one cache across a 256-position chunk boundary of the decode-attention kernel
+        flags = live_split_check(torch, make_instance, shape, blobs, lens, base.seed + 100, xs, args.split, n_split_steps,
+                                 whole=inst, whole_batch=batch)
+        crossed = sum(1 for n in lens if int(n) // 256 != (int(n) + n_split_steps) // 256)
+        split_note = {"split_layer": args.split, "bit_exact_steps": len(flags), "bit_exact": all(flags),
+                      "caches_that_crossed_a_chunk_boundary": crossed}
+        blobs.clear()
+        inst._keep.clear()
+        if not all(flags):
             raise SystemExit("split run is not bit-exact")
-        start = 4
+        note(f"{shape.name}: live split at layer {args.split} bit-exact over {len(flags)} steps")
 
-    for st in range(start, start + args.warmup):
-        inst.run_layers(0, shape.L, batch, xs[st])
-        inst.batch_advance(batch)
-    inst.sync()
-    inst.profile_enable(True)
-    inst.profile_read()
-    t0 = time.perf_counter()
-    for st in range(start + args.warmup, start + args.warmup + args.steps):
-        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
-        inst.batch_advance(batch)
-    inst.sync()
-    torch.cuda.synchronize()
-    total = time.perf_counter() - t0
-    prof = inst.profile_read()
-    inst.profile_enable(False)
-
-    # the profiled steps pay two events per kernel; time the same number of steps again without them
-    t0 = time.perf_counter()
-    for st in range(args.steps):
-        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
-        inst.batch_advance(batch)
-    inst.sync()
-    plain = time.perf_counter() - t0
-
-    d = prof["attn_decode"]
-    achieved = d["bytes"] / (d["ms"] * 1e-3) / 1e9
-    out = base_record("decode tokens/s", B * args.steps / plain, "tokens/s", args, plain / args.steps * 1e3,
+    dec = decode_leg(inst, torch, shape, batch, xs, n_steps, args.steps, args.warmup, n_split_steps, B)
+    out = base_record("decode tokens/s", dec["decode_tokens_per_s"], "tokens/s", args, dec["ms_per_step"],
                       f"{shape.name}-shaped decoder, {shape.L} layers resident, continuous decode of {B} sequences "
                       f"with cache lengths uniform[{lo},{hi}]",
                       {"shape": shape.name, "layers": shape.L, "sequences": B, "mean_cache_len": float(lens.mean())})
-    out.update({
-        "ms_per_step_with_profiling_events": total / args.steps * 1e3,
-        "weights_GB_per_step": shape.L * inst.layer_bytes / 1e9,
-        "kv_GB_per_step": d["bytes"] / args.steps / 1e9,
-        "kernel_ms_per_step": {k: v["ms"] / args.steps for k, v in prof.items() if v["launches"]},
-        "roofline": {"bound": "hbm", "kernel": "attn_decode", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get((shape.name, shape.L, B, "attn_decode")), "launches": d["launches"],
-                     "avg_ms": d["ms"] / d["launches"]},
-    })
+    out.update({k: v for k, v in dec.items() if k not in ("decode_tokens_per_s", "ms_per_step", "steps")})
     if split_note:
         out["split"] = split_note
     if not args.no_cpu_baseline:
@@ -441,6 +526,7 @@ def run_mixed_ttft(args, torch, Instance):
     blobs = [gen_layer_blob_gpu(torch, inst, shape, gen) for _ in range(shape.L)]
     for i in range(16, B):
         fill_kv(torch, inst, shape, gen, i, befores[i])
+    note(f"{shape.name}: {shape.L} pinned layer blobs and the caches of 48 decode sequences ready")
     x0 = torch.from_numpy(W.hidden_bits(shape, T, step=0).view(np.int16).copy()).view(torch.bfloat16).cuda()
     x = torch.empty_like(x0)
     batch = inst.batch(q_start, list(range(B)), befores)
@@ -481,7 +567,7 @@ def run_mixed_ttft(args, torch, Instance):
     ttft = total / args.steps * 1e3
     compute_ms = sum(v["ms"] for v in prof.values()) / args.steps
     ing = float(np.median(ingest_ms))
-    roof, all_tf = gemm_roofline(prof)
+    roof, all_tf = gemm_roofline(prof, shape.name, T)
     out = base_record("prefill tokens/s on partially loaded model", T * args.steps / total, "tokens/s", args, ttft,
                       f"{shape.name}-shaped decoder, layers [0,{resident}) resident and [{resident},{shape.L}) ingested from "
                       f"scale start while one mixed batch (16 prefill requests + 48 decode sequences, {T} rows) runs",
@@ -497,6 +583,64 @@ def run_mixed_ttft(args, torch, Instance):
         out["cpu_baseline"] = cpu_baseline_prefill(base)
     inst.close()
     return out
+
+
+def _release(torch):
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+
+def _leg_summary(rec, keys):
+    out = {"workload": rec["config"]["workload"], "steps": rec["steps"], "warmup": rec["warmup"]}
+    out.update({k: rec[k] for k in keys if k in rec})
+    return out
+
+
+def run_all(args, torch, Instance):
+    """The default line: the 70B-shaped streamed prefill as the headline, the other configurations as extra
+    keys.  --steps / --warmup apply to the headline leg; the secondary legs run their own, smaller counts."""
+    import copy
+    legs = {}
+    a5 = copy.copy(args)
+    a5.shape, a5.requests, a5.fixed_len, a5.distinct_blobs = "70b", 4, 2048, 4
+    head, dec5 = run_prefill_stream(a5, torch, Instance, then_decode=dict(B=32, lo=512, hi=4096, steps=256, warmup=8))
+    legs["cfg5_70b_decode"] = dec5
+    _release(torch)
+    note("headline leg and 70B decode leg done")
+
+    small = min(args.steps, 5)
+    a2 = copy.copy(args)
+    a2.shape, a2.requests, a2.fixed_len, a2.distinct_blobs, a2.steps, a2.warmup, a2.no_cpu_baseline = "7b", 8, 0, 0, small, 2, True
+    r2 = run_prefill_stream(a2, torch, Instance)
+    legs["cfg2_7b_prefill_stream"] = _leg_summary(r2, ["value", "unit", "ms_per_step", "ttft_ms", "ingest_GBps",
+                                                       "resident_prefill_tokens_per_s", "resident_ms",
+                                                       "gemm_TFLOPs_all_classes", "kernel_ms_per_step", "roofline"])
+    legs["cfg2_7b_prefill_stream"]["ingest_streams"] = r2["config"]["ingest_streams"]
+    _release(torch)
+    note("7B streamed prefill leg done")
+
+    a3 = copy.copy(args)
+    a3.shape, a3.requests, a3.fixed_len, a3.steps, a3.warmup, a3.split, a3.no_cpu_baseline = "8b_gqa", 64, 0, 128, 8, 16, args.no_cpu_baseline
+    r3 = run_decode(a3, torch, Instance)
+    legs["cfg3_8b_gqa_decode"] = _leg_summary(r3, ["value", "unit", "ms_per_step", "weights_GB_per_step", "kv_GB_per_step",
+                                                   "hbm_roofline_frac_whole_step", "kernel_ms_per_step", "roofline", "split",
+                                                   "cpu_baseline"])
+    _release(torch)
+    note("8B-GQA decode leg done")
+
+    a4 = copy.copy(args)
+    a4.steps, a4.warmup, a4.no_cpu_baseline = small, 2, True
+    r4 = run_mixed_ttft(a4, torch, Instance)
+    legs["cfg4_13b_mixed_ttft"] = _leg_summary(r4, ["value", "unit", "ms_per_step", "ttft_ms", "ingest_ms", "ingest_GBps",
+                                                    "kernel_ms_sum_per_step", "overlap_efficiency",
+                                                    "gemm_TFLOPs_all_classes", "kernel_ms_per_step", "roofline"])
+    legs["cfg4_13b_mixed_ttft"]["ingest_streams"] = r4["config"]["ingest_streams"]
+    _release(torch)
+    note("13B mixed-batch leg done")
+    head["configs"] = legs
+    return head
 
 
 def run_zigzag(args, torch, Instance):
@@ -567,7 +711,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="prefill_stream", choices=["prefill_stream", "decode", "mixed_ttft", "zigzag"])
+    ap.add_argument("--workload", default="all", choices=["all", "prefill_stream", "decode", "mixed_ttft", "zigzag"])
     ap.add_argument("--shape", default="7b", choices=list(W.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the shape (debugging)")
     ap.add_argument("--requests", type=int, default=8)
@@ -595,7 +739,7 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
-    fn = {"prefill_stream": run_prefill_stream, "decode": run_decode, "mixed_ttft": run_mixed_ttft,
+    fn = {"all": run_all, "prefill_stream": run_prefill_stream, "decode": run_decode, "mixed_ttft": run_mixed_ttft,
           "zigzag": run_zigzag}[args.workload]
     print(json.dumps(fn(args, torch, Instance)))
     return 0
