@@ -207,14 +207,14 @@ def decode_leg(inst, torch, shape, batch, xs, n_steps, steps, warmup, start, B):
     """Timed decode steps on a resident instance: `steps` steps with the library's per-kernel events (for the
     roofline record), then the same number without them (the reported rate)."""
     for st in range(start, start + warmup):
-        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
+        inst.run_layers(0, shape.L, batch, xs[st % n_steps], after_current_stream=False)
         inst.batch_advance(batch)
     inst.sync()
     inst.profile_enable(True)
     inst.profile_read()
     t0 = time.perf_counter()
     for st in range(start + warmup, start + warmup + steps):
-        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
+        inst.run_layers(0, shape.L, batch, xs[st % n_steps], after_current_stream=False)
         inst.batch_advance(batch)
     inst.sync()
     torch.cuda.synchronize()
@@ -223,7 +223,7 @@ def decode_leg(inst, torch, shape, batch, xs, n_steps, steps, warmup, start, B):
     inst.profile_enable(False)
     t0 = time.perf_counter()
     for st in range(steps):
-        inst.run_layers(0, shape.L, batch, xs[st % n_steps])
+        inst.run_layers(0, shape.L, batch, xs[st % n_steps], after_current_stream=False)
         inst.batch_advance(batch)
     inst.sync()
     plain = time.perf_counter() - t0
@@ -288,12 +288,12 @@ def live_split_check(torch, make_instance, shape, blobs, lens, kv_seed, xs, k, s
         b = xs[st].clone()
         c = torch.empty_like(b)
         torch.cuda.synchronize()
-        whole.run_layers(0, shape.L, whole_batch, a)
+        whole.run_layers(0, shape.L, whole_batch, a, after_current_stream=False)
         whole.batch_advance(whole_batch)
-        tgt.run_layers(0, k, batch2, b)
+        tgt.run_layers(0, k, batch2, b, after_current_stream=False)
         tgt.export_boundary(b, B, buf)
         src.import_boundary(c, B, buf)            # the instances share one compute stream: ordered
-        src.run_layers(k, shape.L, batch2, c)
+        src.run_layers(k, shape.L, batch2, c, after_current_stream=False)
         src.batch_advance(batch2)
         whole.sync()
         src.sync()
@@ -351,7 +351,7 @@ def run_prefill_stream(args, torch, Instance, then_decode=None):
                 inst.load_layer_sharded(l, shard_views[l % n_blobs])
             else:
                 inst.load_layer(l, blobs[l % n_blobs])
-        inst.run_layers(0, shape.L, batch, x)
+        inst.run_layers(0, shape.L, batch, x, after_current_stream=False)
 
     def reset():
         for l in range(shape.L):
@@ -386,7 +386,7 @@ def run_prefill_stream(args, torch, Instance, then_decode=None):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(3):
-        inst.run_layers(0, shape.L, batch, x)
+        inst.run_layers(0, shape.L, batch, x, after_current_stream=False)
     inst.sync()
     resident_s = (time.perf_counter() - t0) / 3
 
@@ -465,7 +465,7 @@ def run_decode(args, torch, Instance):
         if args.split:
             blobs.append(blob)            # the split pair loads the same bytes later
         else:
-            inst._keep.clear()            # layer is resident: the staging blob can go
+            inst.drop_sources()           # layer is resident: the staging blob can go
             del blob
     gen_kv = torch.Generator(device="cuda")
     gen_kv.manual_seed(base.seed + 100)
@@ -486,7 +486,7 @@ def run_decode(args, torch, Instance):
         split_note = {"split_layer": args.split, "bit_exact_steps": len(flags), "bit_exact": all(flags),
                       "caches_that_crossed_a_chunk_boundary": crossed}
         blobs.clear()
-        inst._keep.clear()
+        inst.drop_sources()
         if not all(flags):
             raise SystemExit("split run is not bit-exact")
         note(f"{shape.name}: live split at layer {args.split} bit-exact over {len(flags)} steps")
@@ -544,7 +544,7 @@ def run_mixed_ttft(args, torch, Instance):
         inst.reset_clock()
         for l in range(resident, shape.L):
             inst.load_layer(l, blobs[l])
-        inst.run_layers(0, shape.L, batch, x)
+        inst.run_layers(0, shape.L, batch, x, after_current_stream=False)
 
     for _ in range(args.warmup):
         reset()

@@ -3,15 +3,15 @@
  *
  * The paper scales a serving instance by sending it the model one layer at a time and lets the
  * instance execute whatever prefix of layers it already holds, handing the activation to a fully
- * loaded instance at a layer boundary (section 4, "Realizing live autoscale"; section 5.2, "Live
- * autoscale protocol with paired instances").  On one MI355X that becomes:
+ * loaded instance at a layer boundary (section 4, the part on making autoscaling live; section 5.2,
+ * the three-step protocol between a paired new and old instance).  On one MI355X that becomes:
  *
  *   - an *instance*: a weight arena for L decoder layers, a KV cache, two HIP streams;
  *   - *layer ingest*: copy layer i's parameter blob from pinned host memory into HBM in chunks
  *     on the copy stream, mark completion with a per-layer event (the host-memory source of
  *     section 1 / section 5.3's parameter pool, overlapped with execution as in section 4);
- *   - the *frontier*: how many leading layers are resident (an instance "can only execute layers
- *     with parameters loaded", section 1, challenges);
+ *   - the *frontier*: how many leading layers are resident (section 1, challenges: a scaling instance
+ *     can execute only the layers whose parameters it already holds, and that set keeps growing);
  *   - *run layers [a,b)* on a packed batch of hidden states with prefill and/or decode sequences
  *     (section 2.1, layer-by-layer execution with a KV cache held in GPU memory), each layer
  *     gated on its own ingest event;
@@ -171,7 +171,11 @@ int bz_sync(bz_instance* inst);                  /* waits for the copy streams, 
  * arrive one by one).  Enqueues chunked async copies of `n` == layer_bytes bytes from pinned host
  * memory `host` into layer i's slot of the weight arena on the copy stream, records the layer's
  * event and returns at once.  `host` is borrowed until the layer is resident.  Layers may be
- * requested in any order.  BZ_EBUSY if layer i is loading or resident.
+ * requested in any order.  BZ_EBUSY if layer i is loading or resident.  BZ_EINVAL if `host` is not
+ * page-locked memory known to the runtime (from pageable memory every copy would block the caller and
+ * nothing would overlap).  If a HIP call fails while the copies are being enqueued the call returns
+ * BZ_EHIP and the layer is left in a failed state: it cannot run (BZ_ESTATE) or be requested again
+ * (BZ_EBUSY) until bz_unload_layer, which waits for the copies already in flight, has cleared it.
  * The bytes go over in blob order, which is the order the layer reads them (attention weights
  * first, down projection last), and an event is also recorded behind each group of tensors that one
  * stage of the layer needs; bz_run_layers uses them (see there).  See bz_set_ingest_streams for
@@ -188,8 +192,8 @@ int bz_load_layer(bz_instance* inst, int layer, const void* host, size_t n);
 int bz_set_ingest_streams(bz_instance* inst, int n);
 /* Same, from a device buffer (a resident peer's copy: one hop of section 5.1's forwarding chain). */
 int bz_load_layer_from_device(bz_instance* inst, int layer, const void* dev, size_t n);
-/* Parallel sharded transfer (section 5.1, "parallel sharded parameter transfer from multiple
- * sources"): the layer's bytes arrive as n_shards <= BZ_MAX_SHARDS contiguous pieces, each from its
+/* Parallel sharded transfer (section 5.1, the optimisation that sends the shards of a layer from
+ * several sources at once): the layer's bytes arrive as n_shards <= BZ_MAX_SHARDS contiguous pieces, each from its
  * own source buffer, spread over two extra copy streams so that transfers from different sources
  * overlap; the layer's event fires when all of them have landed (the point at which the paper's
  * all-gather has finished).
@@ -205,7 +209,8 @@ typedef struct bz_shard {
     int32_t     reserved_;
 } bz_shard;
 int bz_load_layer_sharded(bz_instance* inst, int layer, const bz_shard* shards, int n_shards);
-/* Forgets layer i (waits for the instance's streams first); it must be loaded again before it can run. */
+/* Forgets layer i (waits for the instance's streams first); it must be loaded again before it can run.
+ * Also the only way out of the failed state a broken-off load leaves. */
 int bz_unload_layer(bz_instance* inst, int layer);
 
 /* Number k of leading layers [0,k) that are resident now.  Never blocks. */
@@ -231,7 +236,8 @@ int bz_kv_release(bz_instance* inst, int slot);
 int64_t bz_kv_free_tokens(bz_instance* inst);    /* largest reservable capacity right now */
 /* Writes / reads n positions starting at pos0 of (layer, slot): k and v are [n, Hkv, d] activation
  * elements, token-major, in host (is_host != 0) or device memory.  Ordered on the compute stream;
- * host transfers complete before return. */
+ * host transfers complete before return and are staged through the instance's workspace (nothing is
+ * allocated), so they must not be issued from another thread while bz_run_layers is being called. */
 int bz_kv_write(bz_instance* inst, int layer, int slot, int pos0, int n, const void* k, const void* v, int is_host);
 int bz_kv_read(bz_instance* inst, int layer, int slot, int pos0, int n, void* k, void* v, int is_host);
 
@@ -239,15 +245,37 @@ int bz_kv_read(bz_instance* inst, int layer, int slot, int pos0, int n, void* k,
 
 /* Builds the device-side description of a packed batch (offsets, per-token sequence ids, attention
  * work lists).  A batch is independent of any instance and can be run by several (the two
- * instances of a split run share one).  The upload is synchronous. */
+ * instances of a split run share one).  This form allocates device memory and uploads synchronously:
+ * for set-up code.  A serving loop whose batch changes every step (section 6, continuous batching)
+ * uses bz_batch_create_in / bz_batch_rebuild below. */
 int bz_batch_create(const bz_batch_desc* desc, bz_batch** out);
+/* The same without allocation and without a blocking copy.  The caller lends `device_mem` (device,
+ * 32-byte aligned, device_bytes >= bz_batch_storage_bytes(...) of the largest batch it will hold) and
+ * `pinned_mem` (page-locked host memory, pinned_bytes >= 2 * device_bytes: two staging halves used in
+ * turn), both until bz_batch_destroy.  The description is laid out in the staging and uploaded with one
+ * asynchronous copy on `stream` (a hipStream_t, normally the compute stream of the instance that runs
+ * the batch next); the call returns at once.  bz_run_layers on an instance whose compute stream is a
+ * different one waits, on the device, for the upload.  BZ_ECAPACITY if the batch does not fit. */
+size_t bz_batch_storage_bytes(int max_seqs, int max_tokens, int max_seq_len);
+int bz_batch_create_in(const bz_batch_desc* desc, void* device_mem, size_t device_bytes, void* pinned_mem,
+                       size_t pinned_bytes, void* stream, bz_batch** out);
+/* Replaces the description of a batch made by bz_batch_create_in (sequences joined or left, new
+ * lengths) in the same storage, asynchronously on `stream`.  Runs already enqueued keep the old
+ * description: the upload is ordered behind them (behind runs on other streams through events).  The
+ * host blocks only if the upload of the last-but-one build has not started yet (two builds ahead of
+ * the device).  A refused description (BZ_EINVAL, BZ_ECAPACITY) leaves the batch as it was;
+ * BZ_ESTATE for a batch that was made by bz_batch_create. */
+int bz_batch_rebuild(bz_batch* batch, const bz_batch_desc* desc, void* stream);
 int bz_batch_destroy(bz_batch* batch);
 int bz_batch_tokens(const bz_batch* batch);
 /* For a batch in which every sequence has exactly one new token: enqueue, on `inst`'s compute
  * stream, kv_len_before[s] += 1 for all s — the next decode step of the same sequences.  The
  * batch's list of cache chunks is rebuilt on the device in the same step; it has room for 16384
- * positions of growth per sequence since bz_batch_create, beyond which the call returns
- * BZ_ECAPACITY and changes nothing (build a new batch). */
+ * positions of growth per sequence since the batch was built (less if lent storage is smaller),
+ * beyond which the call returns BZ_ECAPACITY and changes nothing (build a new batch).
+ * A batch shared by two instances with different compute streams needs no host synchronisation:
+ * the update waits, on the device, for runs of the batch enqueued earlier on the other stream, and
+ * runs enqueued later on the other stream wait for the update. */
 int bz_batch_advance(bz_instance* inst, bz_batch* batch);
 
 /* ---- execution ------------------------------------------------------------------------------ */
@@ -269,12 +297,20 @@ int bz_batch_advance(bz_instance* inst, bz_batch* batch);
  * max_tokens or a sequence outgrows its slot, BZ_ESTATE if a slot of the batch is not reserved. */
 int bz_run_layers(bz_instance* inst, int a, int b, const bz_batch* batch, void* hidden, int flags);
 
-/* Activation hand-off at a layer boundary (section 4: the scaled instance "forwards the
- * activation" to the other one).  Bit-preserving copy of T rows of H activation elements between
+/* Activation hand-off at a layer boundary (section 4, cooperative execution: the scaled instance
+ * passes the activation of its last resident layer on to the loaded one).  Bit-preserving copy of T rows of H activation elements between
  * `hidden` (device) and `buf` (device, or pinned/ordinary host when is_host != 0), ordered on the
  * compute stream.  Host copies complete before return. */
 int bz_export_boundary(bz_instance* inst, const void* hidden, size_t T, void* buf, int is_host);
 int bz_import_boundary(bz_instance* inst, void* hidden, size_t T, const void* buf, int is_host);
+
+/* Ordering against a stream the library does not own.  bz_wait_stream: the compute stream waits for
+ * everything enqueued so far on `stream` (a caller that prepared `hidden` on its own stream calls this
+ * before bz_run_layers).  bz_signal_stream: `stream` waits for everything enqueued so far on the compute
+ * stream (before the caller reads the result on its own stream).  Both are device-side waits and return
+ * at once; a no-op when `stream` is the compute stream. */
+int bz_wait_stream(bz_instance* inst, void* stream);
+int bz_signal_stream(bz_instance* inst, void* stream);
 
 /* ---- counters -------------------------------------------------------------------------------- */
 

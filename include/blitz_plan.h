@@ -1,9 +1,9 @@
-/* Scale-plan generation (section 5.1 of the paper, "Online network-based scale plan generation"):
+/* Scale-plan generation (section 5.1 of the paper, on generating the scale plan online from the network topology):
  * host-only code, no GPU call.  Given the nodes of a cluster, which of them hold the parameters
  * and which are spare, it picks targets and emits serial forwarding chains S -> T1 -> T2 -> ...
  * along which layers are pushed one by one, each node forwarding layer k while receiving k+1.
  *
- * Network model (section 5.1, "Modeling the network between GPUs"): GPUs joined by a scale-up
+ * Network model (section 5.1, the paragraph that models the network between GPUs): GPUs joined by a scale-up
  * fabric form one node and transfers inside it are free; every GPU of a node has a link of
  * `gpu_bw` bytes/s (each direction) to the leaf switch `leaf`; two nodes move data at the smaller
  * of their aggregated bandwidths n_gpus * gpu_bw (each GPU pair carries 1/n of the bytes: the
@@ -20,7 +20,7 @@
  *      in that chain, then lower root id);
  *   4. inside a chain targets are ordered by decreasing link speed from the root (ties: lower id).
  * The tail of each chain forwards to nobody and has the slowest link: the candidate for live
- * scaling (section 5.2, "Selecting instances for live scaling").
+ * scaling (section 5.2, the paragraph on which instances are selected for it).
  *
  * Time model reported with the plan: store-and-forward per layer,
  *   ready(k, l) = max(ready(k-1, l), ready(k, l-1)) + layer_bytes / bw(hop k),

@@ -132,12 +132,17 @@ SIGNATURES = {
     "bz_kv_write": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, C.c_int]),
     "bz_kv_read": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, C.c_int]),
     "bz_batch_create": (C.c_int, [C.POINTER(bz_batch_desc), C.POINTER(_P)]),
+    "bz_batch_storage_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int]),
+    "bz_batch_create_in": (C.c_int, [C.POINTER(bz_batch_desc), _P, C.c_size_t, _P, C.c_size_t, _P, C.POINTER(_P)]),
+    "bz_batch_rebuild": (C.c_int, [_P, C.POINTER(bz_batch_desc), _P]),
     "bz_batch_destroy": (C.c_int, [_P]),
     "bz_batch_tokens": (C.c_int, [_P]),
     "bz_batch_advance": (C.c_int, [_P, _P]),
     "bz_run_layers": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, C.c_int]),
     "bz_export_boundary": (C.c_int, [_P, _P, C.c_size_t, _P, C.c_int]),
     "bz_import_boundary": (C.c_int, [_P, _P, C.c_size_t, _P, C.c_int]),
+    "bz_wait_stream": (C.c_int, [_P, _P]),
+    "bz_signal_stream": (C.c_int, [_P, _P]),
     "bz_stats_read": (C.c_int, [_P, C.POINTER(bz_stats)]),
     "bz_profile_enable": (C.c_int, [_P, C.c_int]),
     "bz_profile_read": (C.c_int, [_P, C.POINTER(bz_profile)]),
@@ -200,21 +205,47 @@ def _i32(a) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
 
 
+def _desc(q_start, seq_slot, kv_len_before):
+    qs, sl, kb = _i32(q_start), _i32(seq_slot), _i32(kv_len_before)
+    if qs.size != sl.size + 1 or kb.size != sl.size:
+        raise ValueError("q_start must have one more entry than seq_slot / kv_len_before")
+    d = bz_batch_desc(int(sl.size), qs.ctypes.data_as(C.POINTER(C.c_int32)), sl.ctypes.data_as(C.POINTER(C.c_int32)),
+                      kb.ctypes.data_as(C.POINTER(C.c_int32)))
+    return d, (qs, sl, kb)
+
+
 class Batch:
-    def __init__(self, lib: C.CDLL, q_start: Sequence[int], seq_slot: Sequence[int], kv_len_before: Sequence[int]):
+    """A packed batch.  With `storage` = (device uint8 tensor, pinned uint8 tensor of twice its size, stream)
+    the batch lives in that memory, is uploaded asynchronously and can be rebuilt in place; without, the
+    library allocates and uploads synchronously."""
+
+    def __init__(self, lib: C.CDLL, q_start: Sequence[int], seq_slot: Sequence[int], kv_len_before: Sequence[int],
+                 storage=None):
         self._lib = lib
-        qs, sl, kb = _i32(q_start), _i32(seq_slot), _i32(kv_len_before)
-        if qs.size != sl.size + 1 or kb.size != sl.size:
-            raise ValueError("q_start must have one more entry than seq_slot / kv_len_before")
-        d = bz_batch_desc(int(sl.size), qs.ctypes.data_as(C.POINTER(C.c_int32)), sl.ctypes.data_as(C.POINTER(C.c_int32)),
-                          kb.ctypes.data_as(C.POINTER(C.c_int32)))
+        d, keep = _desc(q_start, seq_slot, kv_len_before)
         h = _P()
-        rc = lib.bz_batch_create(C.byref(d), C.byref(h))
+        self._storage = storage
+        if storage is None:
+            rc = lib.bz_batch_create(C.byref(d), C.byref(h))
+        else:
+            dev, pinned, stream = storage
+            rc = lib.bz_batch_create_in(C.byref(d), dev.data_ptr(), dev.numel(), pinned.data_ptr(), pinned.numel(),
+                                        stream.cuda_stream if stream is not None else 0, C.byref(h))
         if rc:
             raise BzError(rc, "bz_batch_create", lib.bz_last_hip_error().decode())
         self.handle = h
-        self.T = int(qs[-1])
-        self.B = int(sl.size)
+        self.T = int(keep[0][-1])
+        self.B = int(keep[1].size)
+
+    def rebuild(self, q_start, seq_slot, kv_len_before, stream=None) -> None:
+        d, keep = _desc(q_start, seq_slot, kv_len_before)
+        if stream is None and self._storage is not None:
+            stream = self._storage[2]
+        rc = self._lib.bz_batch_rebuild(self.handle, C.byref(d), stream.cuda_stream if stream is not None else 0)
+        if rc:
+            raise BzError(rc, "bz_batch_rebuild", self._lib.bz_last_hip_error().decode())
+        self.T = int(keep[0][-1])
+        self.B = int(keep[1].size)
 
     def close(self):
         if self.handle:
@@ -244,7 +275,7 @@ class Instance:
         self.layout = bz_layer_layout()
         self._check(self.lib.bz_layer_layout_of(C.byref(cfg), C.byref(self.layout)), "bz_layer_layout_of")
         self.dry_run = dry_run
-        self._keep = []
+        self._keep = {}               # layer -> source buffers borrowed by the library while the layer is loaded
         if not dry_run:
             import torch
             self.torch = torch
@@ -311,25 +342,33 @@ class Instance:
         self._check(self.lib.bz_set_ingest_streams(self.handle, n), "bz_set_ingest_streams")
 
     def load_layer(self, layer: int, pinned) -> None:
-        self._keep.append(pinned)
         self._check(self.lib.bz_load_layer(self.handle, layer, _ptr(pinned), pinned.numel()), "bz_load_layer")
+        self._keep[layer] = [pinned]
 
     def load_layer_from_device(self, layer: int, dev) -> None:
-        self._keep.append(dev)
         self._check(self.lib.bz_load_layer_from_device(self.handle, layer, _ptr(dev), dev.numel()),
                     "bz_load_layer_from_device")
+        self._keep[layer] = [dev]
+
+    def drop_sources(self) -> None:
+        """Lets go of the source buffers of layers that are resident by now (the library borrows a source
+        only until its layer has landed)."""
+        for layer in list(self._keep):
+            if self.layer_ready(layer):
+                del self._keep[layer]
 
     def load_layer_sharded(self, layer: int, shards) -> None:
         """shards: sequence of (source tensor, byte offset in the layer); each source supplies its
         whole length.  Host tensors must be pinned."""
         arr = (bz_shard * len(shards))()
         for j, (t, off) in enumerate(shards):
-            self._keep.append(t)
             arr[j] = bz_shard(_ptr(t), int(off), t.numel() * t.element_size(), 1 if t.is_cuda else 0, 0)
         self._check(self.lib.bz_load_layer_sharded(self.handle, layer, arr, len(shards)), "bz_load_layer_sharded")
+        self._keep[layer] = [t for t, _ in shards]
 
     def unload_layer(self, layer: int) -> None:
         self._check(self.lib.bz_unload_layer(self.handle, layer), "bz_unload_layer")
+        self._keep.pop(layer, None)
 
     def frontier(self) -> int:
         return self._check(self.lib.bz_frontier(self.handle), "bz_frontier")
@@ -375,14 +414,37 @@ class Instance:
         self._check(self.lib.bz_kv_read(self.handle, layer, slot, pos0, n, _ptr(k), _ptr(v), is_host), "bz_kv_read")
 
     # -- batches and execution
-    def batch(self, q_start, seq_slot, kv_len_before) -> Batch:
-        return Batch(self.lib, q_start, seq_slot, kv_len_before)
+    def batch(self, q_start, seq_slot, kv_len_before, storage=None) -> Batch:
+        return Batch(self.lib, q_start, seq_slot, kv_len_before, storage)
+
+    def batch_storage(self, max_seqs: int, max_tokens: int, max_seq_len: int):
+        """Memory for a batch that is built and rebuilt without allocation: (device tensor, pinned tensor of
+        twice the size, this instance's compute stream) for `batch(..., storage=...)`."""
+        n = int(self.lib.bz_batch_storage_bytes(max_seqs, max_tokens, max_seq_len))
+        dev = self.torch.empty(n, dtype=self.torch.uint8, device=self.device)
+        pinned = self.torch.empty(2 * n, dtype=self.torch.uint8, pin_memory=True)
+        return dev, pinned, self.compute_stream
 
     def batch_advance(self, batch: Batch) -> None:
         self._check(self.lib.bz_batch_advance(self.handle, batch.handle), "bz_batch_advance")
 
-    def run_layers(self, a: int, b: int, batch: Batch, hidden, flags: int = 0) -> None:
+    def run_layers(self, a: int, b: int, batch: Batch, hidden, flags: int = 0, after_current_stream: bool = True) -> None:
+        """`hidden` is normally produced on torch's current stream, the layers run on the instance's compute
+        stream: unless told otherwise the compute stream is first made to wait (on the device) for the work
+        enqueued so far on the current stream.  Reading the result needs sync() or signal_stream()."""
+        if after_current_stream:
+            cur = self.torch.cuda.current_stream(self.device)
+            if cur.cuda_stream != self.compute_stream.cuda_stream:
+                self._check(self.lib.bz_wait_stream(self.handle, cur.cuda_stream), "bz_wait_stream")
         self._check(self.lib.bz_run_layers(self.handle, a, b, batch.handle, _ptr(hidden), flags), "bz_run_layers")
+
+    def wait_stream(self, stream) -> None:
+        self._check(self.lib.bz_wait_stream(self.handle, stream.cuda_stream), "bz_wait_stream")
+
+    def signal_stream(self, stream=None) -> None:
+        """Makes `stream` (default: torch's current stream) wait for the compute stream's work so far."""
+        stream = stream or self.torch.cuda.current_stream(self.device)
+        self._check(self.lib.bz_signal_stream(self.handle, stream.cuda_stream), "bz_signal_stream")
 
     def export_boundary(self, hidden, T: int, buf) -> None:
         is_host = int(isinstance(buf, np.ndarray) or (hasattr(buf, "is_cuda") and not buf.is_cuda))

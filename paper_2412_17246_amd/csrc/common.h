@@ -195,6 +195,8 @@ void launch_kv_scatter(const act_t* src_k, const act_t* src_v, const KvView& kv,
 void launch_batch_advance(int32_t* kv_before, int B, const int32_t* decode_seqs, const int32_t* seq_slot, int n_decode,
                           int4* work, int capacity, hipStream_t st);
 
+void launch_set_slot(int32_t* off, int32_t* cap, int32_t off_v, int32_t cap_v, hipStream_t st);
+
 // floats per (decode sequence, query head, chunk) in the decode partial buffer: d outputs, max, sum
 __host__ __device__ inline int decode_partial_stride(int d) { return d + 2; }
 

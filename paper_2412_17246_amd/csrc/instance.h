@@ -19,7 +19,9 @@ struct WsLayout {
     size_t normed, qkv, attn, act, partial, gemm_ws, gemm_ws_bytes, rope, slot_off, slot_cap, total;
 };
 
-enum LayerState { kNone = 0, kLoading = 1, kResident = 2 };
+// kFailed: a HIP call failed while the layer's copies were being enqueued; some of them may be in flight.
+// Only bz_unload_layer, which waits for the streams, clears it.
+enum LayerState { kNone = 0, kLoading = 1, kResident = 2, kFailed = 3 };
 
 struct ProfRec {
     int cls;
@@ -44,6 +46,25 @@ struct bz_batch {
             *d_items = nullptr, *d_decode = nullptr;
     int4* d_work = nullptr;           // decode work list (see BatchView), room for work_capacity entries
     int work_capacity = 0;
+    // storage: either one hipMalloc of the library's (own_dev) or memory the caller lent (bz_batch_create_in)
+    bool own_dev = false;
+    size_t dev_bytes = 0;
+    // caller's pinned host memory the description is laid out in before the upload: two halves of dev_bytes
+    // used in turn, so that the host can lay out the next description while the last upload is still queued
+    void* staging = nullptr;
+    hipEvent_t staged_ev[2] = {nullptr, nullptr};   // upload out of half h has completed
+    bool staged_valid[2] = {false, false};
+    int staging_next = 0;
+    size_t off_words[6] = {0, 0, 0, 0, 0, 0};       // q_start, seq_slot, kv_before, token_seq, items, decode (32-bit words from dev)
+    size_t work_at = 0;                             // byte offset of the work list
+    // Ordering between streams.  A batch may be run by two instances with different compute streams (a split
+    // pair).  Runs that must be ordered against a later device-side change of the batch (advance, rebuild)
+    // leave an event per stream; the change leaves one that later runs on other streams wait for.
+    struct Use { hipStream_t st; hipEvent_t ev; };
+    mutable std::vector<Use> runs;
+    hipStream_t changed_on = nullptr;
+    hipEvent_t changed_ev = nullptr;
+    bool changed_valid = false;
 };
 
 struct bz_instance {
@@ -55,8 +76,8 @@ struct bz_instance {
     bool dry = false;
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
-    // second copy stream (always the library's own), used when ingest_streams == 2: a layer's tensor groups
-    // are then cut in two halves, one per stream (see bz_set_ingest_streams)
+    // second copy stream (always the library's own, created by the first bz_set_ingest_streams(2)): a layer's
+    // tensor groups are then cut in two halves, one per stream
     hipStream_t copy2 = nullptr;
     int ingest_streams = 1;
     unsigned char* weights = nullptr;
@@ -80,4 +101,5 @@ struct bz_instance {
     std::vector<hipEvent_t> ev_pool;
     std::vector<hipStream_t> shard_streams;      // created on first sharded load
     std::vector<hipEvent_t> shard_events;
+    hipEvent_t order_ev = nullptr;               // scratch event of bz_wait_stream / bz_signal_stream
 };

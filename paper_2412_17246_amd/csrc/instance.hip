@@ -193,11 +193,25 @@ struct ProfScope {
     }
 };
 
+// Is `p` page-locked host memory the runtime knows (hipHostMalloc, or registered)?  Pageable memory makes
+// hipMemcpyAsync stage the bytes through a bounce buffer and block the calling thread: the copies would no
+// longer overlap with anything.
+bool is_pinned_host(const void* p) {
+    hipPointerAttribute_t a;
+    memset(&a, 0, sizeof a);
+    if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+        (void)hipGetLastError();             // ordinary malloc memory: the query itself fails
+        return false;
+    }
+    return a.type == hipMemoryTypeHost;
+}
+
 int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpyKind kind) {
     if (!I || !src) return BZ_EINVAL;
     if (layer < 0 || layer >= I->sh.L || n != I->sz.layer_bytes) return BZ_EINVAL;
     if (I->state[layer] != kNone) return BZ_EBUSY;
     if (I->dry) return BZ_ESTATE;
+    if (kind == hipMemcpyHostToDevice && !is_pinned_host(src)) return BZ_EINVAL;
     if (!I->clock_started) {
         HIP_TRY(hipEventRecord(I->t0, I->copy));
         I->clock_started = true;
@@ -209,32 +223,43 @@ int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpy
     // tensors, so that the layer's first stages can run while its MLP weights are still arriving.
     // With two ingest streams each group's bytes are cut in two halves, one per copy stream; the streams
     // never wait for each other inside a layer (a stage of the layer waits for both halves of its group),
-    // only at its end, where the layer's own event is recorded behind both.  With one stream the second
-    // half is empty and its events fire at once.
+    // only at its end, where the layer's own event is recorded behind both.
+    const bool two = I->ingest_streams == 2;
     const size_t ends[4] = {I->lay.wo, I->lay.wg, I->lay.wd, n};
-    size_t start = 0;
-    for (int part = 0; part < 4; ++part) {
-        const size_t mid = start + ((ends[part] - start) / 2 + 255) / 256 * 256;
-        const size_t cut = (I->ingest_streams == 2 && mid < ends[part]) ? mid : ends[part];
-        for (size_t off = start; off < cut;) {
-            const size_t m = cut - off < chunk ? cut - off : chunk;
-            HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy));
-            off += m;
+    auto enqueue = [&]() -> hipError_t {
+        hipError_t e = hipSuccess;
+        size_t start = 0;
+        for (int part = 0; part < 4; ++part) {
+            const size_t mid = start + ((ends[part] - start) / 2 + 255) / 256 * 256;
+            const size_t cut = (two && mid < ends[part]) ? mid : ends[part];
+            for (size_t off = start; off < cut;) {
+                const size_t m = cut - off < chunk ? cut - off : chunk;
+                if ((e = hipMemcpyAsync(dst + off, s + off, m, kind, I->copy)) != hipSuccess) return e;
+                off += m;
+            }
+            for (size_t off = cut; off < ends[part];) {
+                const size_t m = ends[part] - off < chunk ? ends[part] - off : chunk;
+                if ((e = hipMemcpyAsync(dst + off, s + off, m, kind, I->copy2)) != hipSuccess) return e;
+                off += m;
+            }
+            if (two && (e = hipEventRecord(I->ev_part2[4 * layer + part], I->copy2)) != hipSuccess) return e;
+            if (part < 3) {
+                if ((e = hipEventRecord(I->ev_part[3 * layer + part], I->copy)) != hipSuccess) return e;
+            } else {
+                if (two && (e = hipStreamWaitEvent(I->copy, I->ev_part2[4 * layer + part], 0)) != hipSuccess) return e;
+                if ((e = hipEventRecord(I->ev[layer], I->copy)) != hipSuccess) return e;
+            }
+            start = ends[part];
         }
-        for (size_t off = cut; off < ends[part];) {
-            const size_t m = ends[part] - off < chunk ? ends[part] - off : chunk;
-            HIP_TRY(hipMemcpyAsync(dst + off, s + off, m, kind, I->copy2));
-            off += m;
-        }
-        const bool two = I->ingest_streams == 2;
-        if (two) HIP_TRY(hipEventRecord(I->ev_part2[4 * layer + part], I->copy2));
-        if (part < 3) {
-            HIP_TRY(hipEventRecord(I->ev_part[3 * layer + part], I->copy));
-        } else {
-            if (two) HIP_TRY(hipStreamWaitEvent(I->copy, I->ev_part2[4 * layer + part], 0));
-            HIP_TRY(hipEventRecord(I->ev[layer], I->copy));
-        }
-        start = ends[part];
+        return hipSuccess;
+    };
+    const hipError_t e = enqueue();
+    if (e != hipSuccess) {
+        // some chunks may be on their way: the layer can neither run nor be requested again until
+        // bz_unload_layer has waited for the streams
+        I->state[layer] = kFailed;
+        I->parts_valid[layer] = 0;
+        return hip_fail(e, "layer ingest");
     }
     I->parts_valid[layer] = (char)I->ingest_streams;     // 1: group events on the copy stream only; 2: on both streams
     I->state[layer] = kLoading;
@@ -312,6 +337,7 @@ int bz_destroy(bz_instance* I) {
         for (auto& r : I->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
         if (I->t0) (void)hipEventDestroy(I->t0);
         if (I->own_weights && I->weights) (void)hipFree(I->weights);
+        if (I->order_ev) (void)hipEventDestroy(I->order_ev);
         if (I->own_kv && I->kv) (void)hipFree(I->kv);
         if (I->own_ws && I->wsp) (void)hipFree(I->wsp);
         if (I->own_compute && I->compute) (void)hipStreamDestroy(I->compute);
@@ -353,7 +379,6 @@ int bz_create(const bz_config* cfg, bz_instance** out) try {
     else { HIP_TRY_C(hipStreamCreateWithFlags(&I->compute, hipStreamNonBlocking)); I->own_compute = true; }
     if (cfg->copy_stream) I->copy = (hipStream_t)cfg->copy_stream;
     else { HIP_TRY_C(hipStreamCreateWithFlags(&I->copy, hipStreamNonBlocking)); I->own_copy = true; }
-    HIP_TRY_C(hipStreamCreateWithFlags(&I->copy2, hipStreamNonBlocking));
     if (cfg->weights_arena) {
         if (cfg->weights_arena_bytes < I->sz.weights_arena_bytes || ((uintptr_t)cfg->weights_arena & 255)) return fail(BZ_ENOMEM);
         I->weights = (unsigned char*)cfg->weights_arena;
@@ -404,14 +429,18 @@ int bz_create(const bz_config* cfg, bz_instance** out) try {
 int bz_sync(bz_instance* I) {
     if (!I) return BZ_EINVAL;
     if (I->dry) return BZ_OK;
+    // shard streams feed the copy stream through events, so they need no wait of their own
     HIP_TRY(hipStreamSynchronize(I->copy));
-    HIP_TRY(hipStreamSynchronize(I->copy2));
+    if (I->copy2) HIP_TRY(hipStreamSynchronize(I->copy2));
     HIP_TRY(hipStreamSynchronize(I->compute));
     return BZ_OK;
 }
 
 int bz_set_ingest_streams(bz_instance* I, int n) {
     if (!I || (n != 1 && n != 2)) return BZ_EINVAL;
+    // the second stream exists only for instances that ask for it: a process has few hardware queues, and a
+    // split pair of instances would otherwise hold eight streams between them
+    if (n == 2 && !I->dry && !I->copy2) HIP_TRY(hipStreamCreateWithFlags(&I->copy2, hipStreamNonBlocking));
     I->ingest_streams = n;
     return BZ_OK;
 }
@@ -454,26 +483,38 @@ int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int
         HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
         I->shard_events.push_back(e);
     }
+    for (int j = 0; j < n_shards; ++j)
+        if (!shards[j].src_is_device && !is_pinned_host(shards[j].src)) return BZ_EINVAL;
     if (!I->clock_started) {
         HIP_TRY(hipEventRecord(I->t0, I->copy));
         I->clock_started = true;
     }
     const size_t chunk = I->cfg.chunk_bytes > 0 ? (size_t)I->cfg.chunk_bytes : ((size_t)32 << 20);
     unsigned char* dst = layer_ptr(I, layer);
-    for (int j = 0; j < n_shards; ++j) {
-        const bz_shard& sh = shards[j];
-        const unsigned char* s = static_cast<const unsigned char*>(sh.src);
-        const hipMemcpyKind kind = sh.src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
-        for (size_t off = 0; off < sh.bytes; off += chunk) {
-            const size_t m = sh.bytes - off < chunk ? sh.bytes - off : chunk;
-            HIP_TRY(hipMemcpyAsync(dst + sh.offset + off, s + off, m, kind, I->shard_streams[j % n_streams]));
+    auto enqueue = [&]() -> hipError_t {
+        hipError_t e = hipSuccess;
+        for (int j = 0; j < n_shards; ++j) {
+            const bz_shard& sh = shards[j];
+            const unsigned char* s = static_cast<const unsigned char*>(sh.src);
+            const hipMemcpyKind kind = sh.src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+            for (size_t off = 0; off < sh.bytes; off += chunk) {
+                const size_t m = sh.bytes - off < chunk ? sh.bytes - off : chunk;
+                e = hipMemcpyAsync(dst + sh.offset + off, s + off, m, kind, I->shard_streams[j % n_streams]);
+                if (e != hipSuccess) return e;
+            }
         }
+        for (int q = 0; q < n_streams; ++q) {
+            if ((e = hipEventRecord(I->shard_events[q], I->shard_streams[q])) != hipSuccess) return e;
+            if ((e = hipStreamWaitEvent(I->copy, I->shard_events[q], 0)) != hipSuccess) return e;
+        }
+        return hipEventRecord(I->ev[layer], I->copy);        // fires when every shard has landed
+    };
+    const hipError_t e = enqueue();
+    if (e != hipSuccess) {
+        I->state[layer] = kFailed;                           // see enqueue_copy
+        I->parts_valid[layer] = 0;
+        return hip_fail(e, "sharded layer ingest");
     }
-    for (int q = 0; q < n_streams; ++q) {
-        HIP_TRY(hipEventRecord(I->shard_events[q], I->shard_streams[q]));
-        HIP_TRY(hipStreamWaitEvent(I->copy, I->shard_events[q], 0));
-    }
-    HIP_TRY(hipEventRecord(I->ev[layer], I->copy));      // fires when every shard has landed
     I->parts_valid[layer] = 0;                            // shards land in no particular order
     I->state[layer] = kLoading;
     I->stats.bytes_ingested += I->sz.layer_bytes;
@@ -487,8 +528,10 @@ int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int
 
 int bz_unload_layer(bz_instance* I, int layer) {
     if (!I || layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
-    int rc = bz_sync(I);
+    int rc = I->dry ? BZ_OK : bz_sync(I);
     if (rc) return rc;
+    if (I->state[layer] == kFailed)                    // a load that broke off may have left shards in flight that
+        for (hipStream_t q : I->shard_streams) HIP_TRY(hipStreamSynchronize(q));      // nothing on the copy stream waits for
     I->state[layer] = kNone;
     I->parts_valid[layer] = 0;
     return BZ_OK;
@@ -521,7 +564,7 @@ int bz_layer_ready(bz_instance* I, int layer) {
 int bz_wait_layer(bz_instance* I, int layer) {
     if (!I || layer < 0 || layer >= I->sh.L) return BZ_EINVAL;
     if (I->state[layer] == kNone) return BZ_ENOTLOADED;
-    if (I->dry) return BZ_ESTATE;
+    if (I->dry || I->state[layer] == kFailed) return BZ_ESTATE;
     HIP_TRY(hipEventSynchronize(I->ev[layer]));
     I->state[layer] = kResident;
     return BZ_OK;
@@ -559,8 +602,10 @@ static int push_slot(bz_instance* I, int slot) {
     if (I->dry) return BZ_OK;
     const int32_t off = I->slots->reserved(slot) ? (int32_t)I->slots->offset(slot) : 0;
     const int32_t cap = I->slots->reserved(slot) ? (int32_t)I->slots->capacity(slot) : 0;
-    HIP_TRY(hipMemcpy(I->wsp + I->ws.slot_off + (size_t)slot * 4, &off, 4, hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy(I->wsp + I->ws.slot_cap + (size_t)slot * 4, &cap, 4, hipMemcpyHostToDevice));
+    // in stream order on the compute stream, where every kernel that reads the table runs
+    launch_set_slot(reinterpret_cast<int32_t*>(I->wsp + I->ws.slot_off) + slot,
+                    reinterpret_cast<int32_t*>(I->wsp + I->ws.slot_cap) + slot, off, cap, I->compute);
+    HIP_TRY(hipGetLastError());
     return BZ_OK;
 }
 
@@ -605,34 +650,45 @@ static int kv_xfer(bz_instance* I, int layer, int slot, int pos0, int n, const v
     if ((int64_t)pos0 + n > I->slots->capacity(slot) || (int64_t)pos0 + n > I->cfg.max_seq_len) return BZ_ECAPACITY;
     if (I->dry) return BZ_ESTATE;
     if (n == 0) return BZ_OK;
-    const size_t bytes = (size_t)n * I->sh.Hkv * I->sh.d * sizeof(act_t);
     const KvView view = kv_view(I, layer);
     if (!is_host) {
         launch_kv_scatter((const act_t*)k, (const act_t*)v, view, slot, pos0, n, to_cache, (act_t*)ko, (act_t*)vo, I->compute);
         HIP_TRY(hipGetLastError());
         return BZ_OK;
     }
-    unsigned char* tmp = nullptr;
-    HIP_TRY(hipMalloc((void**)&tmp, 2 * bytes));
-    int rc = BZ_OK;
+    // Host side: staged through the activation buffers of the workspace (free between bz_run_layers calls, and
+    // every use here is in stream order on the compute stream), as many positions at a time as fit.
+    unsigned char* stage = I->wsp + I->ws.normed;
+    const size_t span = I->ws.partial - I->ws.normed;
+    const size_t per_tok = (size_t)I->sh.Hkv * I->sh.d * sizeof(act_t);
+    const int step = (int)std::min<size_t>((size_t)n, span / (2 * per_tok));
+    if (step < 1) return BZ_ECAPACITY;
     hipError_t e = hipSuccess;
-    if (to_cache) {
-        e = hipMemcpyAsync(tmp, k, bytes, hipMemcpyHostToDevice, I->compute);
-        if (e == hipSuccess) e = hipMemcpyAsync(tmp + bytes, v, bytes, hipMemcpyHostToDevice, I->compute);
-        if (e == hipSuccess) {
-            launch_kv_scatter((const act_t*)tmp, (const act_t*)(tmp + bytes), view, slot, pos0, n, true, nullptr, nullptr, I->compute);
+    for (int at = 0; at < n && e == hipSuccess; at += step) {
+        const int m = n - at < step ? n - at : step;
+        const size_t mb = (size_t)m * per_tok;
+        act_t* sk = reinterpret_cast<act_t*>(stage);
+        act_t* sv = reinterpret_cast<act_t*>(stage + (size_t)step * per_tok);
+        if (to_cache) {
+            e = hipMemcpyAsync(sk, static_cast<const unsigned char*>(k) + (size_t)at * per_tok, mb, hipMemcpyHostToDevice, I->compute);
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(sv, static_cast<const unsigned char*>(v) + (size_t)at * per_tok, mb, hipMemcpyHostToDevice, I->compute);
+            if (e == hipSuccess) {
+                launch_kv_scatter(sk, sv, view, slot, pos0 + at, m, true, nullptr, nullptr, I->compute);
+                e = hipGetLastError();
+            }
+        } else {
+            launch_kv_scatter(nullptr, nullptr, view, slot, pos0 + at, m, false, sk, sv, I->compute);
             e = hipGetLastError();
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(static_cast<unsigned char*>(ko) + (size_t)at * per_tok, sk, mb, hipMemcpyDeviceToHost, I->compute);
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(static_cast<unsigned char*>(vo) + (size_t)at * per_tok, sv, mb, hipMemcpyDeviceToHost, I->compute);
         }
-    } else {
-        launch_kv_scatter(nullptr, nullptr, view, slot, pos0, n, false, (act_t*)tmp, (act_t*)(tmp + bytes), I->compute);
-        e = hipGetLastError();
-        if (e == hipSuccess) e = hipMemcpyAsync(ko, tmp, bytes, hipMemcpyDeviceToHost, I->compute);
-        if (e == hipSuccess) e = hipMemcpyAsync(vo, tmp + bytes, bytes, hipMemcpyDeviceToHost, I->compute);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(I->compute);
-    if (e != hipSuccess) rc = hip_fail(e, "kv transfer");
-    (void)hipFree(tmp);
-    return rc;
+    if (e != hipSuccess) return hip_fail(e, "kv transfer");
+    return BZ_OK;
 }
 
 int bz_kv_write(bz_instance* I, int layer, int slot, int pos0, int n, const void* k, const void* v, int is_host) {
@@ -645,16 +701,18 @@ int bz_kv_read(bz_instance* I, int layer, int slot, int pos0, int n, void* k, vo
 
 // ---- batches ------------------------------------------------------------------------------
 
-int bz_batch_destroy(bz_batch* b) {
-    if (!b) return BZ_EINVAL;
-    if (b->dev) (void)hipFree(b->dev);
-    delete b;
-    return BZ_OK;
-}
+namespace {
 
-int bz_batch_create(const bz_batch_desc* d, bz_batch** out) try {
-    if (!out) return BZ_EINVAL;
-    *out = nullptr;
+constexpr int kWorkGrowth = 64;          // chunks per decode sequence the work list can grow by before a rebuild
+
+size_t align32(size_t v) { return (v + 31) / 32 * 32; }
+
+// Fills the host side of `b` from a validated description and lays the device image out in `image`
+// (32-bit words; the decode work list starts at byte *work_at).  `max_bytes` (0: no limit) bounds the
+// image: the work list's room for growth shrinks to what fits, and BZ_ECAPACITY is returned if even the
+// present entries do not.
+int describe_batch(const bz_batch_desc* d, bz_batch* b, std::vector<int32_t>& image, size_t max_bytes) {
+    size_t* work_at = &b->work_at;
     if (!d || d->n_seqs < 1 || !d->q_start || !d->seq_slot || !d->kv_len_before) return BZ_EINVAL;
     const int B = d->n_seqs;
     if (d->q_start[0] != 0) return BZ_EINVAL;
@@ -667,13 +725,13 @@ int bz_batch_create(const bz_batch_desc* d, bz_batch** out) try {
     }
     const int T = d->q_start[B];
     if (T < 1) return BZ_EINVAL;
-    bz_batch* b = new (std::nothrow) bz_batch();
-    if (!b) return BZ_ENOMEM;
     b->B = B;
     b->T = T;
     b->q_start.assign(d->q_start, d->q_start + B + 1);
     b->seq_slot.assign(d->seq_slot, d->seq_slot + B);
     b->kv_before.assign(d->kv_len_before, d->kv_len_before + B);
+    b->decode_seqs.clear();
+    b->prefill_sq = 0;
     std::vector<int32_t> token_seq(T), items;
     b->all_decode = true;
     struct Item { int s, qt; long long extent; };
@@ -699,7 +757,8 @@ int bz_batch_create(const bz_batch_desc* d, bz_batch** out) try {
     b->n_decode = (int)b->decode_seqs.size();
 
     // decode work list: one entry per chunk of every decode sequence's cache (the new token included), with
-    // room for kWorkGrowth more chunks per sequence as bz_batch_advance lengthens the caches
+    // room for kWorkGrowth more chunks per sequence as bz_batch_advance lengthens the caches.  The room is
+    // zero-filled, so that a kernel that ran ahead of an update would read a harmless entry, never garbage.
     std::vector<int32_t> work;
     for (int di = 0; di < b->n_decode; ++di) {
         const int s = b->decode_seqs[di];
@@ -710,28 +769,162 @@ int bz_batch_create(const bz_batch_desc* d, bz_batch** out) try {
             work.insert(work.end(), entry, entry + 8);
         }
     }
-    constexpr int kWorkGrowth = 64;
-    b->work_capacity = (int)(work.size() / 8) + kWorkGrowth * b->n_decode;
     const size_t n_i32 = (size_t)(B + 1) + B + B + T + items.size() + b->decode_seqs.size();
-    const size_t work_at = (n_i32 * 4 + 31) / 32 * 32;              // 32-byte entries
-    hipError_t e = hipMalloc(&b->dev, work_at + (size_t)b->work_capacity * 32 + 64);
+    *work_at = align32(n_i32 * 4);
+    const size_t present = work.size() / 8;
+    size_t capacity = present + (size_t)kWorkGrowth * b->n_decode;
+    if (max_bytes) {
+        if (*work_at + present * 32 + 64 > max_bytes) return BZ_ECAPACITY;
+        const size_t fits = (max_bytes - *work_at - 64) / 32;
+        if (capacity > fits) capacity = fits;
+    }
+    b->work_capacity = (int)capacity;
+    image.clear();
+    image.reserve((*work_at + capacity * 32 + 64) / 4);
+    auto put = [&](const std::vector<int32_t>& v) { const size_t at = image.size(); image.insert(image.end(), v.begin(), v.end()); return at; };
+    b->off_words[0] = put(b->q_start);
+    b->off_words[1] = put(b->seq_slot);
+    b->off_words[2] = put(b->kv_before);
+    b->off_words[3] = put(token_seq);
+    b->off_words[4] = put(items);
+    b->off_words[5] = put(b->decode_seqs);
+    image.resize(*work_at / 4, 0);
+    image.insert(image.end(), work.begin(), work.end());
+    image.resize((*work_at + capacity * 32 + 64) / 4, 0);
+    return BZ_OK;
+}
+
+// Device addresses of the arrays, once b->dev is known.
+void bind_batch(bz_batch* b) {
+    int32_t* base = static_cast<int32_t*>(b->dev);
+    b->d_q_start = base + b->off_words[0];
+    b->d_seq_slot = base + b->off_words[1];
+    b->d_kv_before = base + b->off_words[2];
+    b->d_token_seq = base + b->off_words[3];
+    b->d_items = base + b->off_words[4];
+    b->d_decode = base + b->off_words[5];
+    b->d_work = reinterpret_cast<int4*>(static_cast<unsigned char*>(b->dev) + b->work_at);
+}
+
+// Orders stream `st` behind every run of the batch that was enqueued on another stream.
+int wait_for_runs_elsewhere(const bz_batch* b, hipStream_t st) {
+    for (const bz_batch::Use& u : b->runs)
+        if (u.st != st) HIP_TRY(hipStreamWaitEvent(st, u.ev, 0));
+    return BZ_OK;
+}
+
+int mark_changed(bz_batch* b, hipStream_t st) {
+    if (!b->changed_ev) HIP_TRY(hipEventCreateWithFlags(&b->changed_ev, hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(b->changed_ev, st));
+    b->changed_on = st;
+    b->changed_valid = true;
+    return BZ_OK;
+}
+
+}  // namespace
+
+int bz_batch_destroy(bz_batch* b) {
+    if (!b) return BZ_EINVAL;
+    // an upload still reading the caller's staging, or a kernel still reading the device arrays, must not outlive them
+    for (int h = 0; h < 2; ++h) {
+        if (b->staged_valid[h]) (void)hipEventSynchronize(b->staged_ev[h]);
+        if (b->staged_ev[h]) (void)hipEventDestroy(b->staged_ev[h]);
+    }
+    if (b->changed_valid) (void)hipEventSynchronize(b->changed_ev);
+    for (const bz_batch::Use& u : b->runs) { (void)hipEventSynchronize(u.ev); (void)hipEventDestroy(u.ev); }
+    if (b->changed_ev) (void)hipEventDestroy(b->changed_ev);
+    if (b->own_dev && b->dev) (void)hipFree(b->dev);
+    delete b;
+    return BZ_OK;
+}
+
+int bz_batch_create(const bz_batch_desc* d, bz_batch** out) try {
+    if (!out) return BZ_EINVAL;
+    *out = nullptr;
+    bz_batch* b = new (std::nothrow) bz_batch();
+    if (!b) return BZ_ENOMEM;
+    std::vector<int32_t> image;
+    const int rc = describe_batch(d, b, image, 0);
+    if (rc) { delete b; return rc; }
+    hipError_t e = hipMalloc(&b->dev, image.size() * 4);
     if (e != hipSuccess) { hip_fail(e, "hipMalloc(batch)"); delete b; return BZ_EHIP; }
-    std::vector<int32_t> host;
-    host.reserve(n_i32);
-    int32_t* base = (int32_t*)b->dev;
-    auto put = [&](const std::vector<int32_t>& v) { int32_t* at = base + host.size(); host.insert(host.end(), v.begin(), v.end()); return at; };
-    b->d_q_start = put(b->q_start);
-    b->d_seq_slot = put(b->seq_slot);
-    b->d_kv_before = put(b->kv_before);
-    b->d_token_seq = put(token_seq);
-    b->d_items = put(items);
-    b->d_decode = put(b->decode_seqs);
-    e = hipMemcpy(b->dev, host.data(), host.size() * 4, hipMemcpyHostToDevice);
-    b->d_work = reinterpret_cast<int4*>(static_cast<unsigned char*>(b->dev) + work_at);
-    if (e == hipSuccess && !work.empty()) e = hipMemcpy(b->d_work, work.data(), work.size() * 4, hipMemcpyHostToDevice);
+    b->own_dev = true;
+    b->dev_bytes = image.size() * 4;
+    bind_batch(b);
+    e = hipMemcpy(b->dev, image.data(), image.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { hip_fail(e, "hipMemcpy(batch)"); bz_batch_destroy(b); return BZ_EHIP; }
     *out = b;
     return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
+}
+
+size_t bz_batch_storage_bytes(int max_seqs, int max_tokens, int max_seq_len) {
+    if (max_seqs < 1 || max_tokens < 1 || max_seq_len < 1) return 0;
+    const size_t B = (size_t)max_seqs, T = (size_t)max_tokens;
+    const size_t items = 2 * (T / kPrefillTileQ + B);                        // (sequence, query tile) pairs
+    const size_t words = (B + 1) + B + B + T + items + B;
+    const size_t chunks = ((size_t)max_seq_len + kDecodeChunk) / kDecodeChunk;  // of a cache of max_seq_len positions
+    return align32(words * 4) + B * (chunks + kWorkGrowth) * 32 + 64;
+}
+
+static int build_in_place(bz_batch* b, const bz_batch_desc* d, hipStream_t st) {
+    const int h = b->staging_next;
+    // the upload that last used this half of the staging (two builds ago) must have left it ...
+    if (b->staged_valid[h]) HIP_TRY(hipEventSynchronize(b->staged_ev[h]));
+    // ... and runs enqueued on other streams must have read the device arrays before the new ones land
+    int rc = wait_for_runs_elsewhere(b, st);
+    if (rc) return rc;
+    if (b->changed_valid && b->changed_on != st) HIP_TRY(hipStreamWaitEvent(st, b->changed_ev, 0));
+    std::vector<int32_t> image;
+    rc = describe_batch(d, b, image, b->dev_bytes);
+    if (rc) return rc;
+    bind_batch(b);
+    unsigned char* half = static_cast<unsigned char*>(b->staging) + (size_t)h * b->dev_bytes;
+    memcpy(half, image.data(), image.size() * 4);
+    HIP_TRY(hipMemcpyAsync(b->dev, half, image.size() * 4, hipMemcpyHostToDevice, st));
+    if (!b->staged_ev[h]) HIP_TRY(hipEventCreateWithFlags(&b->staged_ev[h], hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(b->staged_ev[h], st));
+    b->staged_valid[h] = true;
+    b->staging_next = h ^ 1;
+    return mark_changed(b, st);
+}
+
+int bz_batch_create_in(const bz_batch_desc* d, void* device_mem, size_t device_bytes, void* pinned_mem, size_t pinned_bytes,
+                       void* stream, bz_batch** out) try {
+    if (!out) return BZ_EINVAL;
+    *out = nullptr;
+    if (!device_mem || !pinned_mem || ((uintptr_t)device_mem & 31) || ((uintptr_t)pinned_mem & 3)) return BZ_EINVAL;
+    if (device_bytes < 128 || pinned_bytes < 2 * device_bytes) return BZ_EINVAL;
+    if (!d || d->n_seqs < 1) return BZ_EINVAL;
+    if (!is_pinned_host(pinned_mem)) return BZ_EINVAL;
+    bz_batch* b = new (std::nothrow) bz_batch();
+    if (!b) return BZ_ENOMEM;
+    b->dev = device_mem;
+    b->dev_bytes = device_bytes;
+    b->staging = pinned_mem;
+    const int rc = build_in_place(b, d, (hipStream_t)stream);
+    if (rc) { bz_batch_destroy(b); return rc; }
+    *out = b;
+    return BZ_OK;
+} catch (const std::bad_alloc&) {
+    return BZ_ENOMEM;
+} catch (...) {
+    return BZ_EINVAL;
+}
+
+int bz_batch_rebuild(bz_batch* b, const bz_batch_desc* d, void* stream) try {
+    if (!b || !d) return BZ_EINVAL;
+    if (!b->staging) return BZ_ESTATE;                 // only batches that live in caller memory can be rebuilt
+    {   // validate first: a refused description must leave the batch as it was
+        bz_batch probe;
+        std::vector<int32_t> image;
+        const int rc = describe_batch(d, &probe, image, b->dev_bytes);
+        if (rc) return rc;
+    }
+    return build_in_place(b, d, (hipStream_t)stream);
 } catch (const std::bad_alloc&) {
     return BZ_ENOMEM;
 } catch (...) {
@@ -747,9 +940,15 @@ int bz_batch_advance(bz_instance* I, bz_batch* b) {
     long long work = 0;                  // entries of the work list after this step
     for (int s : b->decode_seqs) work += (b->kv_before[s] + 2 + kDecodeChunk - 1) / kDecodeChunk;
     if (work > b->work_capacity) return BZ_ECAPACITY;
+    // runs of this batch enqueued on another instance's stream still read the lengths and the work list
+    int rc = wait_for_runs_elsewhere(b, I->compute);
+    if (rc) return rc;
+    if (b->changed_valid && b->changed_on != I->compute) HIP_TRY(hipStreamWaitEvent(I->compute, b->changed_ev, 0));
     launch_batch_advance(b->d_kv_before, b->B, b->d_decode, b->d_seq_slot, b->n_decode, b->d_work, b->work_capacity,
                          I->compute);
     HIP_TRY(hipGetLastError());
+    rc = mark_changed(b, I->compute);
+    if (rc) return rc;
     for (auto& v : b->kv_before) v += 1;
     return BZ_OK;
 }
@@ -768,8 +967,10 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         if ((int64_t)batch->kv_before[s] + qlen > I->slots->capacity(slot)) return BZ_ECAPACITY;
         if ((int64_t)batch->kv_before[s] + qlen > I->cfg.max_seq_len) return BZ_ECAPACITY;
     }
-    for (int l = a; l < b; ++l)
+    for (int l = a; l < b; ++l) {
         if (I->state[l] == kNone) return BZ_ENOTLOADED;
+        if (I->state[l] == kFailed) return BZ_ESTATE;
+    }
     if (I->dry) return BZ_ESTATE;
     if (flags & BZ_RUN_NOWAIT) {
         for (int l = a; l < b; ++l) {
@@ -780,6 +981,8 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
     }
     const Shape& sh = I->sh;
     const int T = batch->T;
+    // the batch's device arrays may have been uploaded, or advanced, on another instance's stream
+    if (batch->changed_valid && batch->changed_on != I->compute) HIP_TRY(hipStreamWaitEvent(I->compute, batch->changed_ev, 0));
     const BatchView bv = batch_view(batch);
     act_t* x = static_cast<act_t*>(hidden);
     act_t* normed = reinterpret_cast<act_t*>(I->wsp + I->ws.normed);
@@ -870,6 +1073,20 @@ int bz_run_layers(bz_instance* I, int a, int b, const bz_batch* batch, void* hid
         launch_reduce_residual_rmsnorm(x, gws, pending_down, nullptr, normed, T, sh.H, I->cfg.rms_eps, st);
         HIP_TRY(hipGetLastError());
     }
+    if (batch->all_decode || batch->staging) {
+        // this batch can change on the device later (advance, rebuild), possibly on another stream: leave a
+        // marker behind the kernels that read it (one event per stream that ever ran it, re-recorded)
+        bz_batch::Use* use = nullptr;
+        for (bz_batch::Use& u : batch->runs)
+            if (u.st == st) use = &u;
+        if (!use) {
+            hipEvent_t ev = nullptr;
+            HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+            batch->runs.push_back(bz_batch::Use{st, ev});
+            use = &batch->runs.back();
+        }
+        HIP_TRY(hipEventRecord(use->ev, st));
+    }
     I->stats.tokens_run += (uint64_t)T * (uint64_t)(b - a);
     I->stats.layer_launches += (uint64_t)(b - a);
     return BZ_OK;
@@ -898,6 +1115,26 @@ int bz_import_boundary(bz_instance* I, void* hidden, size_t T, const void* buf, 
     if (bytes == 0) return BZ_OK;
     HIP_TRY(hipMemcpyAsync(hidden, buf, bytes, is_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice, I->compute));
     if (is_host) HIP_TRY(hipStreamSynchronize(I->compute));
+    return BZ_OK;
+}
+
+int bz_wait_stream(bz_instance* I, void* stream) {
+    if (!I) return BZ_EINVAL;
+    if (I->dry) return BZ_ESTATE;
+    if ((hipStream_t)stream == I->compute) return BZ_OK;
+    if (!I->order_ev) HIP_TRY(hipEventCreateWithFlags(&I->order_ev, hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(I->order_ev, (hipStream_t)stream));
+    HIP_TRY(hipStreamWaitEvent(I->compute, I->order_ev, 0));
+    return BZ_OK;
+}
+
+int bz_signal_stream(bz_instance* I, void* stream) {
+    if (!I) return BZ_EINVAL;
+    if (I->dry) return BZ_ESTATE;
+    if ((hipStream_t)stream == I->compute) return BZ_OK;
+    if (!I->order_ev) HIP_TRY(hipEventCreateWithFlags(&I->order_ev, hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(I->order_ev, I->compute));
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, I->order_ev, 0));
     return BZ_OK;
 }
 

@@ -427,6 +427,19 @@ __global__ __launch_bounds__(256) void batch_advance_kernel(int32_t* kv_before, 
     }
 }
 
+// Slot table entry of one KV slot, written in stream order (a host-to-device copy of four bytes would
+// block the calling thread).
+__global__ void set_slot_kernel(int32_t* off, int32_t* cap, int32_t off_v, int32_t cap_v) {
+    if (threadIdx.x == 0) {
+        *off = off_v;
+        *cap = cap_v;
+    }
+}
+
+void launch_set_slot(int32_t* off, int32_t* cap, int32_t off_v, int32_t cap_v, hipStream_t st) {
+    hipLaunchKernelGGL(set_slot_kernel, dim3(1), dim3(64), 0, st, off, cap, off_v, cap_v);
+}
+
 void launch_batch_advance(int32_t* kv_before, int B, const int32_t* decode_seqs, const int32_t* seq_slot, int n_decode,
                           int4* work, int capacity, hipStream_t st) {
     hipLaunchKernelGGL(batch_advance_kernel, dim3(1), dim3(256), 0, st, kv_before, B, decode_seqs, seq_slot, n_decode, work,
