@@ -16,9 +16,8 @@ namespace bz {
 // Loads of cache contents that are read once per step (decode attention): non-temporal, so that the
 // stream does not push through the caches what nobody will read again; on this chip a streaming read
 // of that kind runs about a quarter faster than a default one.
-#ifndef BZ_STREAM_LOAD
-#define BZ_STREAM_LOAD(ptr) __builtin_nontemporal_load(ptr)
-#endif
+template <class T>
+__device__ __forceinline__ T stream_load(const T* ptr) { return __builtin_nontemporal_load(ptr); }
 
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -393,7 +392,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                kf[rb][ks] = BZ_STREAM_LOAD(reinterpret_cast<const bf16x8*>(Kc + boff[rb] + ((ks * 2 + lh) * 32 + lq) * 8));
+                kf[rb][ks] = stream_load(reinterpret_cast<const bf16x8*>(Kc + boff[rb] + ((ks * 2 + lh) * 32 + lq) * 8));
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -401,7 +400,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
                     vf[rb][tt][db] =
-                        BZ_STREAM_LOAD(reinterpret_cast<const bf16x8*>(Vc + boff[rb] + ((2 * tt + lh) * D + db * 32 + lq) * 8));
+                        stream_load(reinterpret_cast<const bf16x8*>(Vc + boff[rb] + ((2 * tt + lh) * D + db * 32 + lq) * 8));
         bf16x8 qf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {

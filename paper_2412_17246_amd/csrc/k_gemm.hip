@@ -2,9 +2,11 @@
 // the matrix cores (v_mfma_f32_32x32x16_bf16), and three epilogues: plain, + residual, SwiGLU.
 //
 // Both operands are K-contiguous, so a lane's MFMA operand (8 consecutive k of one row / column)
-// is one 16-byte LDS read.  Tiles are staged global -> registers -> LDS, double buffered, one
-// barrier per 64-wide K step; LDS rows are padded by 16 bytes so the 16-byte operand reads of 16
-// consecutive rows fall in distinct banks.
+// is one 16-byte LDS read.  Three kernels share the work: gemm_big_kernel (prefill-sized problems: 256x256
+// tiles, operands global -> LDS by DMA into a five-slot ring), gemm_skinny_kernel (up to 256 rows: the
+// weights are streamed once, split over K) and gemm_kernel below (everything else: K tails, odd widths,
+// no workspace), which stages tiles global -> registers -> LDS, double buffered, one barrier per 64-wide
+// K step, LDS rows padded by 16 bytes so that the operand reads of 16 consecutive rows fall in distinct banks.
 #include <type_traits>
 
 #include "common.h"
@@ -231,12 +233,10 @@ __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-#ifndef BZ_BIG_WN
-#define BZ_BIG_WN 2
-#endif
+// Waves along the output-feature dimension: 2, i.e. four waves of 128x128 each, one per SIMD.  (Four - eight
+// waves of 128x64, two per SIMD - was measured slower: its LDS operand reads fill the LDS port.)
+constexpr int kBigWN = 2;
 
-// WN = waves along the output-feature dimension: 2 (4 waves, 128x128 per wave) or 4 (8 waves, two per
-// SIMD, 128x64 per wave).
 // logical tile id -> tile coordinates: groups of 4 tile rows, walked column by column, so that the
 // tiles running together on an XCD share operand rows in its L2
 // Which feature sits where.  A 32x32x16 MFMA leaves lane half h of the output with rows 8g + 4h + 0..3 of
@@ -726,8 +726,8 @@ template <int MODE>
 static bool big_available() {
     constexpr int LDS = kBigSlots * kBigSlot;
     static LdsLimit whole, partial;
-    const bool a = whole.raise(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, false>), LDS);
-    const bool b = partial.raise(reinterpret_cast<const void*>(gemm_big_kernel<MODE, BZ_BIG_WN, true>), LDS);
+    const bool a = whole.raise(reinterpret_cast<const void*>(gemm_big_kernel<MODE, kBigWN, false>), LDS);
+    const bool b = partial.raise(reinterpret_cast<const void*>(gemm_big_kernel<MODE, kBigWN, true>), LDS);
     return a && b;
 }
 
@@ -735,8 +735,8 @@ template <int MODE>
 static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int M, int N, int K, float* ws,
                        size_t ws_bytes, hipStream_t st) {
     constexpr int LDS = kBigSlots * kBigSlot;
-    auto kern = gemm_big_kernel<MODE, BZ_BIG_WN, false>;
-    auto kern_part = gemm_big_kernel<MODE, BZ_BIG_WN, true>;
+    auto kern = gemm_big_kernel<MODE, kBigWN, false>;
+    auto kern_part = gemm_big_kernel<MODE, kBigWN, true>;
     BigPlan p = big_plan(MODE, M, N, K);
     if (p.tail > 0 && (ws == nullptr || ws_bytes < p.ws_bytes)) {     // no scratch: every tile whole
         p.n_dp = p.tiles_m * p.tiles_n;
@@ -744,17 +744,17 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
         p.splits = 1;
     }
     if (p.n_dp > 0)
-        hipLaunchKernelGGL(kern, dim3(p.n_dp), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K, p.tiles_m, p.tiles_n,
+        hipLaunchKernelGGL(kern, dim3(p.n_dp), dim3(128 * kBigWN), LDS, st, a, w, r, c, M, N, K, p.tiles_m, p.tiles_n,
                            p.n_dp, p.splits, ws);
     if (p.tail > 0) {
-        hipLaunchKernelGGL(kern_part, dim3(p.tail * p.splits), dim3(128 * BZ_BIG_WN), LDS, st, a, w, r, c, M, N, K,
+        hipLaunchKernelGGL(kern_part, dim3(p.tail * p.splits), dim3(128 * kBigWN), LDS, st, a, w, r, c, M, N, K,
                            p.tiles_m, p.tiles_n, p.n_dp, p.splits, ws);
-        constexpr int kUnits = 2 * BZ_BIG_WN * ((MODE == 2) ? 4 / BZ_BIG_WN : 8 / BZ_BIG_WN) * 16;   // waves * blocks * (i, g)
+        constexpr int kUnits = 2 * kBigWN * ((MODE == 2) ? 4 / kBigWN : 8 / kBigWN) * 16;   // waves * blocks * (i, g)
         if ((N & 7) == 0)
-            hipLaunchKernelGGL((gemm_big_fixup<MODE, BZ_BIG_WN, true>), dim3(p.tail, kUnits / 8), dim3(256), 0, st, ws, r, c,
+            hipLaunchKernelGGL((gemm_big_fixup<MODE, kBigWN, true>), dim3(p.tail, kUnits / 8), dim3(256), 0, st, ws, r, c,
                                M, N, p.tiles_m, p.tiles_n, p.n_dp, p.splits);
         else
-            hipLaunchKernelGGL((gemm_big_fixup<MODE, BZ_BIG_WN, false>), dim3(p.tail, kUnits / 4), dim3(256), 0, st, ws, r, c,
+            hipLaunchKernelGGL((gemm_big_fixup<MODE, kBigWN, false>), dim3(p.tail, kUnits / 4), dim3(256), 0, st, ws, r, c,
                                M, N, p.tiles_m, p.tiles_n, p.n_dp, p.splits);
     }
 }
@@ -782,21 +782,15 @@ static void launch_big(const bf16* a, const bf16* w, const bf16* r, bf16* c, int
 template <int RB, int TB> struct SkCfg {
     static constexpr int kXBytes = 64 * TB * kBK * (int)sizeof(bf16);         // activations of a stage: 8 KiB * TB
     static constexpr int kStage = kXBytes + 64 * RB * kBK * (int)sizeof(bf16);  // + weights 8 KiB * RB
-#ifndef BZ_SK2_STAGES
-#define BZ_SK2_STAGES 5
-#endif
-    static constexpr int kStages = (RB == 1 && TB == 1) ? 4 : BZ_SK2_STAGES;
+    static constexpr int kStages = (RB == 1 && TB == 1) ? 4 : 5;
     static constexpr int kLds = kStage * kStages;
     static constexpr int kPerCu = kLds * 2 <= 160 * 1024 ? 2 : 1;
     static constexpr int kSlots = 256 * kPerCu;                               // workgroups the chip holds at a time
 };
-#ifndef BZ_SK_STREAM_MIB
-#define BZ_SK_STREAM_MIB 64
-#endif
 // Weight matrices from this size on count as long streams: RB = 2, and loads with the non-temporal cache
 // policy (read once per step; streamed that way a long read runs faster - gate/up of the 8B shape -6 % -
 // a short one does not or gets slower).
-constexpr size_t kSkStreamBytes = (size_t)BZ_SK_STREAM_MIB << 20;
+constexpr size_t kSkStreamBytes = (size_t)64 << 20;
 
 // vmcnt(n) lgkmcnt(0), n < 64
 __device__ __forceinline__ constexpr int sk_wait(int n) { return ((n >> 4) << 14) | 0x0070 | (n & 15); }
@@ -1081,11 +1075,9 @@ static SkinnyPlan skinny_plan(int M, int N, int K, int mode) {
 // Beyond 64 rows a workgroup covers 128.  Against the large-tile kernel with every tile split (the four
 // projections of the 8B-GQA shape, us): 65 rows 118 / 167, 128 rows 130 / 182, 192 rows 207 / 204,
 // 256 rows 215 / 228; with three blocks (384 rows) it loses, 319 / 250.
-#ifndef BZ_SK_MAX_M
-#define BZ_SK_MAX_M 256
-#endif
+constexpr int kSkMaxM = 256;
 static bool skinny_ok(int M, int N, int K) {
-    return M >= 1 && M <= BZ_SK_MAX_M && K % kBK == 0 && N % 4 == 0 &&
+    return M >= 1 && M <= kSkMaxM && K % kBK == 0 && N % 4 == 0 &&
            (uint64_t)2 * N * K < 0x7fffffffull;          // 32-bit byte offsets into the weights (2N rows in gate/up mode)
 }
 
