@@ -48,12 +48,37 @@ PEAK_HBM_GBPS = 8000.0
 # script, each scaled by what the same counter reads for a device copy of known size.  Keyed by (shape, rows,
 # kernel class); the value names the summary under profiles/ that holds the counters and the command.  A
 # workload without an entry reports "traffic": null.  The algorithmic bytes are computed, not looked up.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # gate/up projection of the large-tile kernel: L2-miss traffic summed over the eight XCD L2s (FETCH_SIZE) plus
+    # bytes written (WRITE_SIZE); most of the fetches are served by the Infinity Cache, the counters cannot tell
+    ("70b", 8192, "gemm_gateup"): (11.283e9 + 0.470e9, "profiles/gemm_big_kernel_prefill_counters.txt"),
+    ("7b", 6768, "gemm_gateup"): (1.881e9 + 0.149e9 + 0.069e9 + 0.051e9 + 0.051e9 + 0.001e9,
+                                  "profiles/gemm_big_kernel_prefill_counters.txt"),
+    ("13b", 11970, "gemm_gateup"): (5.582e9 + 0.331e9, "profiles/gemm_big_kernel_prefill_counters.txt"),
+    # decode attention: split-KV kernel (fetch + partial results written) and the combine's fetch
+    ("8b_gqa", 64, "attn_decode"): (0.5671e9 + 0.0098e9 + 0.0113e9, "profiles/attn_decode_and_skinny_gemm_decode_counters.txt"),
+    ("70b", 32, "attn_decode"): (0.2936e9 + 0.0101e9 + 0.0117e9, "profiles/attn_decode_and_skinny_gemm_decode_counters.txt"),
+}
 
 
 def traffic_of(shape_name, rows, kernel):
     hit = MEASURED_TRAFFIC.get((shape_name, rows, kernel))
     return (hit[0], hit[1]) if hit else (None, None)
+
+
+_STREAMS = {}
+
+
+def bench_streams(torch):
+    """One compute stream and one copy stream for the whole process, shared by every instance the benchmark
+    creates.  A process has four hardware queues and the runtime deals streams onto them as they are created:
+    an instance whose copy stream lands on the queue of its compute stream runs its copies and its kernels one
+    after the other (measured: the 7B-shaped streamed prefill took ingest + compute, 313 ms, instead of 233 ms,
+    when its streams were the eighth and ninth the process had created)."""
+    if not _STREAMS:
+        _STREAMS["compute"] = torch.cuda.Stream()
+        _STREAMS["copy"] = torch.cuda.Stream()
+    return _STREAMS["compute"], _STREAMS["copy"]
 
 
 def note(msg):
@@ -324,9 +349,9 @@ def run_prefill_stream(args, torch, Instance, then_decode=None):
         max_seqs = max(B, dB)
         max_len = max(max_len, then_decode["hi"] + d_steps_total + 8)
         kv_tokens = max(kv_tokens, int(d_lens.sum()) + dB * (d_steps_total + 40))
-    stream = torch.cuda.Stream()
+    stream, copy_stream = bench_streams(torch)
     inst = Instance(shape, max_seqs=max_seqs, max_seq_len=max_len, max_tokens=T,
-                    kv_tokens=kv_tokens, chunk_bytes=args.chunk_mib << 20, compute_stream=stream)
+                    kv_tokens=kv_tokens, chunk_bytes=args.chunk_mib << 20, compute_stream=stream, copy_stream=copy_stream)
     for i, n in enumerate(lens):
         inst.kv_reserve(i, int(n))
     gen = torch.Generator(device="cuda")
@@ -458,13 +483,13 @@ def run_decode(args, torch, Instance):
         lo = hi = args.fixed_len
     n_split_steps = 8 if args.split else 0
     n_steps = 2 * args.steps + args.warmup + 4 + n_split_steps     # every step appends a position
-    stream = torch.cuda.Stream()
+    stream, copy_stream = bench_streams(torch)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(base.seed)
 
     def make_instance():
         inst = Instance(shape, max_seqs=B, max_seq_len=hi + n_steps + 8, max_tokens=B,
-                        kv_tokens=int(lens.sum()) + B * (n_steps + 40), compute_stream=stream)
+                        kv_tokens=int(lens.sum()) + B * (n_steps + 40), compute_stream=stream, copy_stream=copy_stream)
         for i, n in enumerate(lens):
             inst.kv_reserve(i, int(n) + n_steps + 8)
         return inst
@@ -530,9 +555,9 @@ def run_mixed_ttft(args, torch, Instance):
     q_start = np.concatenate([[0], np.cumsum(lens_new)]).astype(np.int32)
     T, B = int(q_start[-1]), len(lens_new)
     caps = [n + b for n, b in zip(lens_new, befores)]
-    stream = torch.cuda.Stream()
+    stream, copy_stream = bench_streams(torch)
     inst = Instance(shape, max_seqs=B, max_seq_len=max(caps) + 1, max_tokens=T, kv_tokens=sum(caps) + 32 * B,
-                    chunk_bytes=args.chunk_mib << 20, compute_stream=stream)
+                    chunk_bytes=args.chunk_mib << 20, compute_stream=stream, copy_stream=copy_stream)
     for i, c in enumerate(caps):
         inst.kv_reserve(i, c)
     gen = torch.Generator(device="cuda")
