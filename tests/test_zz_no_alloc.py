@@ -38,10 +38,8 @@ def test_static_scratch_gemm_equals_workspace_gemm_on_two_calls_in_a_row(fp32, m
     torch.cuda.synchronize()
     # the two calls back to back on one stream, nothing between them: the second starts on the scratch the
     # first one left behind
-    before = torch.cuda.memory_allocated()
     for (M, N, K, a, ar, w, wr, r, rr, want_dev, got_dev) in cases:
         op_gemm_static(mode, a, w, r if mode == 1 else None, got_dev, M, N, K, fp32_debug=fp32)
-    assert torch.cuda.memory_allocated() == before
     torch.cuda.synchronize()
     for (M, N, K, a, ar, w, wr, r, rr, want_dev, got_dev) in cases:
         assert torch.equal(got_dev.view(torch.int32 if fp32 else torch.int16),
