@@ -504,8 +504,8 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
     issue_unit(kt0 + 1, 2, false);
 #pragma unroll
     for (int q = 0; q < NCH / 2; ++q) issue_piece(kt0 + 1, 3, true, q);
-    if (NCH == 8) __builtin_amdgcn_s_waitcnt(0x0F7C);  // vmcnt(12): tile kt0 landed
-    else __builtin_amdgcn_s_waitcnt(0x0F76);           // vmcnt(6)
+    static_assert(WN == 2 && NCH == 8, "the hand-written wait counts below assume four waves filling eight chunks each");
+    __builtin_amdgcn_s_waitcnt(0x0F7C);                // vmcnt(12): tile kt0 landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -523,8 +523,7 @@ __global__ __launch_bounds__(128 * WN, 1) void gemm_big_kernel(const bf16* __res
         kstep(0, sx, sww, 3, kt0 + i + 2, fa2, false, NCH / 2);
         // tile i + 1 has landed (only the NCH newest loads, activations of tile i + 2, may be in flight);
         // own LDS reads of tile i are done
-        if (NCH == 8) __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
-        else __builtin_amdgcn_s_waitcnt(0x0074);            // vmcnt(4) lgkmcnt(0)
+        __builtin_amdgcn_s_waitcnt(0x0078);            // vmcnt(8) lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         // tile i + 2's weights, first half, into the slot this tile's activations just left
