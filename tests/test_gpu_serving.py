@@ -187,3 +187,42 @@ def test_ingest_sources_must_be_page_locked(torch):
     inst.drop_sources()
     assert not inst._keep
     inst.close()
+
+
+def test_batch_storage_bound_holds_for_the_extreme_batches(torch):
+    """bz_batch_storage_bytes(max_seqs, max_tokens, max_seq_len) is enough for every batch within those limits:
+    all sequences decoding on caches of the maximum length, one token per sequence of prefill, one long
+    prefill, and the mix; a batch beyond the limits is refused, not truncated."""
+    from paper_2412_17246_amd import load_library
+    from paper_2412_17246_amd.binding import Batch
+    lib = load_library(False)
+    max_seqs, max_tokens, max_seq_len = 48, 4096, 2048
+    n = int(lib.bz_batch_storage_bytes(max_seqs, max_tokens, max_seq_len))
+    assert n > 0 and n % 32 == 0
+    assert lib.bz_batch_storage_bytes(0, 1, 1) == 0 and lib.bz_batch_storage_bytes(1, 0, 1) == 0
+    dev = torch.empty(n, dtype=torch.uint8, device="cuda")
+    pinned = torch.empty(2 * n, dtype=torch.uint8, pin_memory=True)
+    st = torch.cuda.Stream()
+    slots = list(range(max_seqs))
+    cases = [
+        (list(range(max_seqs + 1)), slots, [max_seq_len - 1] * max_seqs),                 # all decode, longest caches
+        ([0, max_tokens], [0], [0]),                                                       # one long prefill
+        ([0] + [2 * (i + 1) for i in range(max_seqs)], slots, [0] * max_seqs),            # many two-token prefills
+        ([0, max_tokens - (max_seqs - 1)] + [max_tokens - (max_seqs - 1) + i for i in range(1, max_seqs)], slots,
+         [0] + [max_seq_len - 1] * (max_seqs - 1)),                                        # one prefill + the rest decoding
+    ]
+    held = None
+    for q, sl, kb in cases:
+        if held is None:
+            held = Batch(lib, q, sl, kb, storage=(dev, pinned, st))
+        else:
+            held.rebuild(q, sl, kb)
+        assert held.T == q[-1] and held.B == len(sl)
+    st.synchronize()
+    with pytest.raises(Exception) as ei:                                                   # 64 x the tokens the storage was sized for
+        held.rebuild([0, 64 * max_tokens], [0], [0])
+    assert "BZ_ECAPACITY" in str(ei.value)
+    assert held.T == cases[-1][0][-1]                                                      # the refused description changed nothing
+    held.close()
+    with pytest.raises(Exception):                                                         # staging too small for two halves
+        Batch(lib, [0, 1], [0], [0], storage=(dev, pinned[:n], st))
