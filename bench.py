@@ -544,6 +544,104 @@ def run_decode(args, torch, Instance):
     return out
 
 
+def run_continuous(args, torch, Instance):
+    """Continuous batching (paper section 6): a decode loop whose membership changes every step - one sequence
+    leaves, one with a cache of its own joins.  Three ways to tell the library: (a) membership frozen, the batch
+    advanced on the device (lower bound on the step time); (b) one batch object in lent memory rebuilt in place
+    every step, asynchronously; (c) a new batch per step with the allocating, synchronous call (the only way
+    before the in-place form existed).  Reports ms per step and the host time spent enqueueing a step."""
+    base = W.CONFIGS[args.shape if args.shape != "7b" else "8b_gqa"]
+    shape = with_layers(base, args.layers)
+    B = args.requests if args.requests != 8 else 64
+    pool = B + 32                                     # slots: B active + spares that rotate in
+    lens = W.uniform_lengths(base.seed, pool, 256, 4096)
+    steps = args.steps
+    stream, copy_stream = bench_streams(torch)
+    inst = Instance(shape, max_seqs=pool, max_seq_len=4096 + 3 * steps + 16, max_tokens=B,
+                    kv_tokens=int(lens.sum()) + pool * (3 * steps + 48), compute_stream=stream, copy_stream=copy_stream)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(base.seed)
+    for l in range(shape.L):
+        blob = gen_layer_blob_gpu(torch, inst, shape, gen, pinned=False)
+        torch.cuda.synchronize()
+        inst.load_layer_from_device(l, blob)
+        inst.sync()
+        inst.drop_sources()
+        del blob
+    gen_kv = torch.Generator(device="cuda")
+    gen_kv.manual_seed(base.seed + 100)
+    for i, n in enumerate(lens):
+        inst.kv_reserve(i, int(n) + 3 * steps + 16)
+        fill_kv(torch, inst, shape, gen_kv, i, int(n))
+    note(f"{shape.name}: {shape.L} layers resident, caches of {pool} sequences filled")
+    xs = torch.randn(8, B, shape.H, generator=gen, device="cuda").to(torch.bfloat16)
+    cur = [int(n) for n in lens]                      # cache length per slot, as the host tracks it
+    q = list(range(B + 1))
+    torch.cuda.synchronize()
+
+    def members(step):                                # slots active at `step`: a window sliding over the pool
+        return [(step + j) % pool for j in range(B)]
+
+    out = {}
+    # (a) frozen membership, device-side advance
+    batch = inst.batch(q, members(0), [cur[s] for s in members(0)])
+    for _ in range(4):
+        inst.run_layers(0, shape.L, batch, xs[0], after_current_stream=False)
+        inst.batch_advance(batch)
+    inst.sync()
+    t0 = time.perf_counter()
+    for st in range(steps):
+        inst.run_layers(0, shape.L, batch, xs[st % 8], after_current_stream=False)
+        inst.batch_advance(batch)
+    host = time.perf_counter() - t0
+    inst.sync()
+    out["frozen_membership_advance"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
+                                        "host_enqueue_ms_per_step": host / steps * 1e3}
+    for s in members(0):
+        cur[s] += steps + 4
+    batch.close()
+    # (b) rebuilt in place every step
+    storage = inst.batch_storage(B, B, 4096 + 3 * steps + 16)
+    batch = inst.batch(q, members(0), [cur[s] for s in members(0)], storage=storage)
+    t0 = time.perf_counter()
+    for st in range(steps):
+        m = members(st)
+        if st:
+            batch.rebuild(q, m, [cur[s] for s in m])
+        inst.run_layers(0, shape.L, batch, xs[st % 8], after_current_stream=False)
+        for s in m:
+            cur[s] += 1
+    host = time.perf_counter() - t0
+    inst.sync()
+    out["rebuilt_in_place"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
+                               "host_enqueue_ms_per_step": host / steps * 1e3}
+    batch.close()
+    # (c) a new allocated batch per step
+    t0 = time.perf_counter()
+    old = []
+    for st in range(steps):
+        m = members(st)
+        b2 = inst.batch(q, m, [cur[s] for s in m])
+        inst.run_layers(0, shape.L, b2, xs[st % 8], after_current_stream=False)
+        for s in m:
+            cur[s] += 1
+        old.append(b2)                                # destroying it here would wait for the step
+    host = time.perf_counter() - t0
+    inst.sync()
+    out["new_batch_per_step"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
+                                 "host_enqueue_ms_per_step": host / steps * 1e3}
+    for b2 in old:
+        b2.close()
+    rec = base_record("decode tokens/s", B / (out["rebuilt_in_place"]["ms_per_step"] * 1e-3), "tokens/s", args,
+                      out["rebuilt_in_place"]["ms_per_step"],
+                      f"{shape.name}-shaped decoder, {shape.L} layers resident, continuous batching of {B} sequences out of a "
+                      f"pool of {pool}: one leaves and one joins every step, the batch rebuilt in place",
+                      {"shape": shape.name, "layers": shape.L, "sequences": B, "pool": pool})
+    rec["modes"] = out
+    inst.close()
+    return rec
+
+
 def run_mixed_ttft(args, torch, Instance):
     base = W.CONFIGS["13b"]
     shape = with_layers(base, args.layers)
@@ -751,7 +849,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="all", choices=["all", "prefill_stream", "decode", "mixed_ttft", "zigzag"])
+    ap.add_argument("--workload", default="all", choices=["all", "prefill_stream", "decode", "mixed_ttft", "zigzag", "continuous"])
     ap.add_argument("--shape", default="7b", choices=list(W.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the shape (debugging)")
     ap.add_argument("--requests", type=int, default=8)
@@ -769,7 +867,7 @@ def main() -> int:
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         return 2
     if args.steps is None:
-        args.steps = 128 if args.workload == "decode" else 5
+        args.steps = 128 if args.workload in ("decode", "continuous") else 5
     if args.warmup is None:
         args.warmup = 8 if args.workload == "decode" else 2
 
@@ -780,7 +878,7 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     fn = {"all": run_all, "prefill_stream": run_prefill_stream, "decode": run_decode, "mixed_ttft": run_mixed_ttft,
-          "zigzag": run_zigzag}[args.workload]
+          "zigzag": run_zigzag, "continuous": run_continuous}[args.workload]
     print(json.dumps(fn(args, torch, Instance)))
     return 0
 
