@@ -427,6 +427,9 @@ def run_prefill_stream(args, torch, Instance, then_decode=None):
     roof_res, all_tf_res = gemm_roofline(prof_res, shape.name, T)
 
     roof, all_tf = gemm_roofline(prof, shape.name, T)
+    roof["note"] = ("timed (streamed) steps: the compute stream idles between layers while the host link is the bottleneck, "
+                    "and a launch after an idle gap runs at the clock the power management fell back to; the same launches "
+                    "back to back are in roofline_back_to_back")
     out = base_record("prefill tokens/s on partially loaded model", T * args.steps / total, "tokens/s", args,
                       ms_per_step,
                       f"{shape.name}-shaped decoder, {shape.L} layers streamed from pinned host memory while a packed "
