@@ -273,3 +273,25 @@ def test_scale_plan_argument_checks():
         with pytest.raises(B.BzError) as e:
             B.plan_generate(bad_nodes, *args)
         assert e.value.name == "BZ_EINVAL", (bad_nodes, args)
+
+
+@pytest.mark.parametrize("libname", ["libblitzlayer.so", "libblitzlayer_fp32dbg.so"])
+def test_headers_compile_as_c_and_the_library_serves_a_plain_c_program(tmp_path, libname):
+    """include/*.h are C headers: a C99 program (tests/c_abi/dry_run.c) is compiled with gcc -pedantic, linked
+    against the library with no Python in the process, and exercises the GPU-free calls."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2412_17246_amd")
+    exe = str(tmp_path / "dry_run")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+           os.path.join(root, "tests", "c_abi", "dry_run.c"), "-o", exe, "-L", pkg, "-l:" + libname,
+           "-Wl,-rpath," + pkg, "-Wl,-rpath,/opt/rocm/lib"]
+    if libname.endswith("fp32dbg.so"):
+        cmd.insert(1, "-DEXPECT_FP32_DEBUG")
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert run.returncode == 0 and "all checks passed" in run.stdout, run.stdout + run.stderr
