@@ -586,57 +586,64 @@ def run_continuous(args, torch, Instance):
         return [(step + j) % pool for j in range(B)]
 
     out = {}
-    # (a) frozen membership, device-side advance
-    batch = inst.batch(q, members(0), [cur[s] for s in members(0)])
-    for _ in range(4):
-        inst.run_layers(0, shape.L, batch, xs[0], after_current_stream=False)
-        inst.batch_advance(batch)
-    inst.sync()
-    t0 = time.perf_counter()
-    for st in range(steps):
-        inst.run_layers(0, shape.L, batch, xs[st % 8], after_current_stream=False)
-        inst.batch_advance(batch)
-    host = time.perf_counter() - t0
-    inst.sync()
-    out["frozen_membership_advance"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
-                                        "host_enqueue_ms_per_step": host / steps * 1e3}
-    for s in members(0):
-        cur[s] += steps + 4
-    batch.close()
-    # (b) rebuilt in place every step
-    storage = inst.batch_storage(B, B, 4096 + 3 * steps + 16)
-    batch = inst.batch(q, members(0), [cur[s] for s in members(0)], storage=storage)
-    t0 = time.perf_counter()
-    for st in range(steps):
-        m = members(st)
-        if st:
-            batch.rebuild(q, m, [cur[s] for s in m])
-        inst.run_layers(0, shape.L, batch, xs[st % 8], after_current_stream=False)
-        for s in m:
-            cur[s] += 1
-    host = time.perf_counter() - t0
-    inst.sync()
-    out["rebuilt_in_place"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
-                               "host_enqueue_ms_per_step": host / steps * 1e3}
-    batch.close()
-    # (c) a new allocated batch per step
-    t0 = time.perf_counter()
-    old = []
-    for st in range(steps):
-        m = members(st)
-        b2 = inst.batch(q, m, [cur[s] for s in m])
-        inst.run_layers(0, shape.L, b2, xs[st % 8], after_current_stream=False)
-        for s in m:
-            cur[s] += 1
-        old.append(b2)                                # destroying it here would wait for the step
-    host = time.perf_counter() - t0
-    inst.sync()
-    out["new_batch_per_step"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
-                                 "host_enqueue_ms_per_step": host / steps * 1e3}
-    for b2 in old:
-        b2.close()
-    rec = base_record("decode tokens/s", B / (out["rebuilt_in_place"]["ms_per_step"] * 1e-3), "tokens/s", args,
-                      out["rebuilt_in_place"]["ms_per_step"],
+    modes = set(args.continuous_modes.split(","))
+    if not modes or not modes <= {"frozen", "in_place", "new"}:
+        raise SystemExit("--continuous-modes takes a comma-separated subset of frozen,in_place,new")
+    if "frozen" in modes:
+        # (a) frozen membership, device-side advance
+        batch = inst.batch(q, members(0), [cur[s] for s in members(0)])
+        for _ in range(4):
+            inst.run_layers(0, shape.L, batch, xs[0], after_current_stream=False)
+            inst.batch_advance(batch)
+        inst.sync()
+        t0 = time.perf_counter()
+        for st in range(steps):
+            inst.run_layers(0, shape.L, batch, xs[st % 8], after_current_stream=False)
+            inst.batch_advance(batch)
+        host = time.perf_counter() - t0
+        inst.sync()
+        out["frozen_membership_advance"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
+                                            "host_enqueue_ms_per_step": host / steps * 1e3}
+        for s in members(0):
+            cur[s] += steps + 4
+        batch.close()
+    if "in_place" in modes:
+        # (b) rebuilt in place every step
+        storage = inst.batch_storage(B, B, 4096 + 3 * steps + 16)
+        batch = inst.batch(q, members(0), [cur[s] for s in members(0)], storage=storage)
+        t0 = time.perf_counter()
+        for st in range(steps):
+            m = members(st)
+            if st:
+                batch.rebuild(q, m, [cur[s] for s in m])
+            inst.run_layers(0, shape.L, batch, xs[st % 8], after_current_stream=False)
+            for s in m:
+                cur[s] += 1
+        host = time.perf_counter() - t0
+        inst.sync()
+        out["rebuilt_in_place"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
+                                   "host_enqueue_ms_per_step": host / steps * 1e3}
+        batch.close()
+    if "new" in modes:
+        # (c) a new allocated batch per step
+        t0 = time.perf_counter()
+        old = []
+        for st in range(steps):
+            m = members(st)
+            b2 = inst.batch(q, m, [cur[s] for s in m])
+            inst.run_layers(0, shape.L, b2, xs[st % 8], after_current_stream=False)
+            for s in m:
+                cur[s] += 1
+            old.append(b2)                                # destroying it here would wait for the step
+        host = time.perf_counter() - t0
+        inst.sync()
+        out["new_batch_per_step"] = {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3,
+                                     "host_enqueue_ms_per_step": host / steps * 1e3}
+        for b2 in old:
+            b2.close()
+    head = out.get("rebuilt_in_place") or next(iter(out.values()))
+    rec = base_record("decode tokens/s", B / (head["ms_per_step"] * 1e-3), "tokens/s", args,
+                      head["ms_per_step"],
                       f"{shape.name}-shaped decoder, {shape.L} layers resident, continuous batching of {B} sequences out of a "
                       f"pool of {pool}: one leaves and one joins every step, the batch rebuilt in place",
                       {"shape": shape.name, "layers": shape.L, "sequences": B, "pool": pool})
@@ -863,6 +870,8 @@ def main() -> int:
     ap.add_argument("--shards", type=int, default=1, help="prefill_stream: ingest every layer as this many parallel shards")
     ap.add_argument("--split", type=int, default=0, help="decode: also run a live split at this layer and compare bits")
     ap.add_argument("--chunk-mib", type=int, default=0, help="ingest chunk size in MiB (0 = library default)")
+    ap.add_argument("--continuous-modes", default="frozen,in_place,new",
+                    help="continuous: which of the three ways to run (a trace of one way alone shows its host calls)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
