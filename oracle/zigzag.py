@@ -23,7 +23,12 @@ Readings of points the text leaves open (the figure with the pseudocode is not a
     free at the same instant, the source chooses first;
   - the source never takes a request while the target is in the middle of one of its layers: it
     waits for that layer to end (it does not skip ahead in the queue: FCFS);
-  - ZigZag puts no cap on the number of layers a request may run on the target.
+  - ZigZag puts no cap on the number of layers a request may run on the target;
+  - `layer_time` (section 5.4, the retrofit for LLMs): the time of a layer grows with the number of
+    batched tokens, so every request batch gets a factor of its own, found by profiling; here
+    layer_time[r] is the time ONE layer of request r takes on either instance (default 1 for all:
+    the section 5.2 model).  Loading times stay in the same absolute unit.  The decision rules do
+    not change; only the durations do.
 
 Pins (tests/test_oracle_zigzag.py, values in tests/golden/zigzag_example.txt): the paper's worked
 example (7 layers, loading a layer takes 6 layer-times) - request 1 gets (1,6), requests 2 and 3
@@ -35,7 +40,9 @@ once and in order, no layer executed on the target before it is resident, neithe
 two things at once, FCFS completion order on the source); limits (infinitely slow loading ->
 everything after layer 0 on the source; instant loading and a busy source -> everything on the
 target); the program's constraints against hand-enumerated tiny cases and against the example's own
-configurations; the ILP-free policy against the best of all fixed configurations on tiny cases.
+configurations; the ILP-free policy against the best of all fixed configurations on tiny cases;
+per-request layer times against two timelines worked out by hand, against the unit-time schedule
+when all factors are equal (times scale, configurations do not change) and against the invariants.
 
 Parity unpinned (stated by the paper, not reproduced under these readings, reported by the tests):
   - "(2,5)" as the FINAL configuration of requests 4 and 5: the ILP-free rule gives (3,4) and (4,3);
@@ -85,7 +92,17 @@ def _first_starts(spans: List[Span], n: int) -> List[float]:
     return [min(sp.start for sp in spans if sp.request == r) for r in range(n)]
 
 
-def simulate_zigzag(L: int, n_requests: int, load_time: float, source_free_at: float = 0.0) -> Schedule:
+def _layer_times(n_requests: int, layer_time) -> List[float]:
+    if layer_time is None:
+        return [1.0] * n_requests
+    w = [float(x) for x in layer_time]
+    assert len(w) == n_requests and all(x > 0 for x in w)
+    return w
+
+
+def simulate_zigzag(L: int, n_requests: int, load_time: float, source_free_at: float = 0.0,
+                    layer_time=None) -> Schedule:
+    w = _layer_times(n_requests, layer_time)
     done = [0] * n_requests              # layers finished so far
     owner = [None] * n_requests          # "source" once the source has taken the request
     finish = [None] * n_requests
@@ -113,18 +130,18 @@ def simulate_zigzag(L: int, n_requests: int, load_time: float, source_free_at: f
                 owner[head] = "source"
                 remaining = L - done[head]
                 if remaining > 0:
-                    spans.append(Span(t, t + remaining, "source", head, done[head], L))
-                source_free = t + remaining
-                finish[head] = t + remaining
+                    spans.append(Span(t, t + remaining * w[head], "source", head, done[head], L))
+                source_free = t + remaining * w[head]
+                finish[head] = t + remaining * w[head]
         # then the target: first request in FCFS order whose next layer is resident
         if target_job is None and target_free <= t:
             avail = _loaded(t, load_time, L)
             pick = next((r for r in range(n_requests)
                          if finish[r] is None and owner[r] is None and done[r] < avail), None)
             if pick is not None:
-                spans.append(Span(t, t + 1, "target", pick, done[pick], done[pick] + 1))
-                target_job = (pick, t + 1)
-                target_free = t + 1
+                spans.append(Span(t, t + w[pick], "target", pick, done[pick], done[pick] + 1))
+                target_job = (pick, t + w[pick])
+                target_free = t + w[pick]
         # advance to the next event
         cand = []
         if target_job is not None:
@@ -145,19 +162,21 @@ def simulate_zigzag(L: int, n_requests: int, load_time: float, source_free_at: f
                     first_start=_first_starts(spans, n_requests))
 
 
-def simulate_best_effort(L: int, n_requests: int, load_time: float, source_free_at: float = 0.0) -> Schedule:
+def simulate_best_effort(L: int, n_requests: int, load_time: float, source_free_at: float = 0.0,
+                         layer_time=None) -> Schedule:
+    w = _layer_times(n_requests, layer_time)
     half = max(1, L // 2)
     T, S, finish, spans = [], [], [], []
     t_target = 0.0
     t_source = float(source_free_at)
     for r in range(n_requests):
         k = max(1, min(_loaded(t_target, load_time, L), half))
-        spans.append(Span(t_target, t_target + k, "target", r, 0, k))
-        handed = t_target + k
+        spans.append(Span(t_target, t_target + k * w[r], "target", r, 0, k))
+        handed = t_target + k * w[r]
         t_target = handed
         start = max(t_source, handed)
-        spans.append(Span(start, start + (L - k), "source", r, k, L))
-        t_source = start + (L - k)
+        spans.append(Span(start, start + (L - k) * w[r], "source", r, k, L))
+        t_source = start + (L - k) * w[r]
         T.append(k)
         S.append(L - k)
         finish.append(t_source)

@@ -98,15 +98,17 @@ def test_third_and_fourth_layer_of_requests_4_and_5_are_what_yields_32_to_22():
     assert s.finish[5] - s.first_start[5] == 22
 
 
-def _check_schedule(s, L, n, load_time):
+def _check_schedule(s, L, n, load_time, layer_time=None):
+    w = [1.0] * n if layer_time is None else list(layer_time)
     per_req = {r: [] for r in range(n)}
     for sp in s.spans:
         assert sp.end > sp.start
+        assert abs((sp.end - sp.start) - (sp.layer_b - sp.layer_a) * w[sp.request]) < 1e-9    # a layer of request r takes w[r]
         per_req[sp.request].append(sp)
         if sp.instance == "target":
             # no layer runs on the target before it is resident
             for k in range(sp.layer_a, sp.layer_b):
-                t_k = sp.start + (k - sp.layer_a)
+                t_k = sp.start + (k - sp.layer_a) * w[sp.request]
                 assert load_time <= 0 or t_k >= k * load_time - 1e-9, (sp, k)
     for r, spans in per_req.items():
         spans.sort(key=lambda x: x.start)
@@ -132,6 +134,48 @@ def _check_schedule(s, L, n, load_time):
 def test_invariants(L, n, load, free):
     _check_schedule(Z.simulate_zigzag(L, n, load, free), L, n, load)
     _check_schedule(Z.simulate_best_effort(L, n, load, free), L, n, load)
+
+
+def test_layer_times_per_request_on_timelines_worked_out_by_hand():
+    # Section 5.4: a layer of request r takes layer_time[r] (the batch's token count decides it).
+    # (i) ZigZag, L = 4, a layer arrives every 3, source free at 2, layer times (1, 2):
+    #   0..1  target runs layer 0 of request 0;  1..3 layer 0 of request 1 (layer 1 is not there yet)
+    #   2     the source is free, takes request 0 (the target is busy with request 1): layers 1..3, 2..5
+    #   3     layer 1 is resident: target runs layer 1 of request 1, 3..5
+    #   5     the source is free again, takes request 1 with two layers left: 2 * 2 -> 5..9
+    s = Z.simulate_zigzag(4, 2, 3, source_free_at=2, layer_time=[1, 2])
+    assert (s.T, s.finish, s.first_start) == ([1, 2], [5, 9], [0, 1])
+    # (ii) ZigZag, L = 3, a layer arrives every 2, idle source, layer times (2, 1): the source takes request 0 whole
+    #   (0..6); the target runs request 1 alone, one layer as each arrives: 0..1, 2..3, 4..5
+    s = Z.simulate_zigzag(3, 2, 2, source_free_at=0, layer_time=[2, 1])
+    assert (s.T, s.finish) == ([0, 3], [6, 5])
+    # (iii) best effort, the setting of (i): request 0 one layer (0..1) then the source 2..5; request 1 is dispatched
+    #   at 1 with one layer resident: 1..3, then waits for the source: 5..11
+    b = Z.simulate_best_effort(4, 2, 3, source_free_at=2, layer_time=[1, 2])
+    assert (b.T, b.finish) == ([1, 1], [5, 11])
+
+
+@pytest.mark.parametrize("L,n,load,free", [(7, 7, 6, 1), (5, 6, 2, 3), (8, 4, 3, 0.5)])
+@pytest.mark.parametrize("c", [0.5, 4.0])
+def test_equal_layer_times_only_change_the_unit_of_time(L, n, load, free, c):
+    # every layer takes c: the timeline is the unit-time one with the clock scaled by c
+    for sim in (Z.simulate_zigzag, Z.simulate_best_effort):
+        unit = sim(L, n, load, free)
+        scaled = sim(L, n, load * c, free * c, layer_time=[c] * n)
+        assert scaled.T == unit.T
+        assert scaled.finish == [f * c for f in unit.finish]
+        assert scaled.first_start == [f * c for f in unit.first_start]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants_with_layer_times(seed):
+    import random
+    rnd = random.Random(seed)
+    L, n = rnd.randint(2, 9), rnd.randint(1, 8)
+    load, free = rnd.choice([0.5, 1, 2.25, 6]), rnd.choice([0, 0.75, 3, 10])
+    w = [rnd.choice([0.25, 0.5, 1, 1.5, 3]) for _ in range(n)]
+    _check_schedule(Z.simulate_zigzag(L, n, load, free, layer_time=w), L, n, load, w)
+    _check_schedule(Z.simulate_best_effort(L, n, load, free, layer_time=w), L, n, load, w)
 
 
 def test_limits_with_closed_forms():
