@@ -350,6 +350,13 @@ typedef struct bz_zz_event {
  * the source.  Same decision code as bz_zz_run. */
 int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, double source_free_at,
                    int32_t* layers_on_target, double* finish_time);
+/* The same with a time per layer for every request (section 5.4: the time of a layer grows with the
+ * number of batched tokens, so the formulation gets one factor per request batch, found by profiling):
+ * one layer of request r takes layer_time[r] (host, [n_requests], each > 0 and finite) on either
+ * instance, in the unit load_time and source_free_at are given in.  The decision rules are those of
+ * bz_zz_simulate; NULL means 1 for every request.  BZ_EINVAL for a factor that is not positive. */
+int bz_zz_simulate_weighted(int policy, int n_layers, int n_requests, double load_time, double source_free_at,
+                            const double* layer_time, int32_t* layers_on_target, double* finish_time);
 
 /* A scheduler over two instances holding the same model (the source fully resident; the target
  * loading: the caller issues bz_load_layer on it before or while bz_zz_run runs).  Both instances

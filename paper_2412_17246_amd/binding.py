@@ -148,6 +148,8 @@ SIGNATURES = {
     "bz_profile_read": (C.c_int, [_P, C.POINTER(bz_profile)]),
     "bz_zz_simulate": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.POINTER(C.c_int32),
                                  C.POINTER(C.c_double)]),
+    "bz_zz_simulate_weighted": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.POINTER(C.c_double),
+                                          C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "bz_zz_create": (C.c_int, [_P, _P, C.c_int, C.POINTER(_P)]),
     "bz_zz_destroy": (C.c_int, [_P]),
     "bz_zz_submit": (C.c_int, [_P, _P, _P, _P]),
@@ -471,12 +473,19 @@ class Instance:
 
 
 def zz_simulate(policy: int, n_layers: int, n_requests: int, load_time: float, source_free_at: float = 0.0,
-                fp32_debug: bool = False):
-    """Virtual-time run of the scheduler's decision code: (layers on target, finish time) per request."""
+                fp32_debug: bool = False, layer_time: Optional[Sequence[float]] = None):
+    """Virtual-time run of the scheduler's decision code: (layers on target, finish time) per request.
+    layer_time: time of one layer of each request (default: 1 for all)."""
     lib = load_library(fp32_debug)
     T = (C.c_int32 * n_requests)()
     fin = (C.c_double * n_requests)()
-    rc = lib.bz_zz_simulate(policy, n_layers, n_requests, load_time, source_free_at, T, fin)
+    if layer_time is None:
+        rc = lib.bz_zz_simulate(policy, n_layers, n_requests, load_time, source_free_at, T, fin)
+    else:
+        if len(layer_time) != n_requests:
+            raise ValueError("layer_time needs one entry per request")
+        w = (C.c_double * n_requests)(*[float(x) for x in layer_time])
+        rc = lib.bz_zz_simulate_weighted(policy, n_layers, n_requests, load_time, source_free_at, w, T, fin)
     if rc:
         raise BzError(rc, "bz_zz_simulate")
     return list(T), list(fin)

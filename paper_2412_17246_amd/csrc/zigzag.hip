@@ -81,10 +81,21 @@ struct bz_zz {
 extern "C" {
 
 int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, double source_free_at,
-                   int32_t* T_out, double* finish_out) try {
+                   int32_t* T_out, double* finish_out) {
+    return bz_zz_simulate_weighted(policy, n_layers, n_requests, load_time, source_free_at, nullptr, T_out, finish_out);
+}
+
+int bz_zz_simulate_weighted(int policy, int n_layers, int n_requests, double load_time, double source_free_at,
+                            const double* layer_time, int32_t* T_out, double* finish_out) try {
     if (n_layers < 1 || n_requests < 1 || !T_out || !finish_out || load_time < 0 || source_free_at < 0) return BZ_EINVAL;
     if (policy != BZ_ZZ_ZIGZAG && policy != BZ_ZZ_BEST_EFFORT) return BZ_EINVAL;
     const int L = n_layers, N = n_requests;
+    std::vector<double> w(N, 1.0);                 // time of one layer of request r
+    if (layer_time)
+        for (int r = 0; r < N; ++r) {
+            if (!(layer_time[r] > 0) || layer_time[r] > 1e300) return BZ_EINVAL;      // also refuses NaN
+            w[r] = layer_time[r];
+        }
     if (policy == BZ_ZZ_BEST_EFFORT) {
         const int half = L / 2 > 1 ? L / 2 : 1;
         double t_target = 0, t_source = source_free_at;
@@ -92,10 +103,10 @@ int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, d
             int k = resident_at(t_target, load_time, L);
             if (k > half) k = half;
             if (k < 1) k = 1;
-            const double handed = t_target + k;
+            const double handed = t_target + k * w[r];
             t_target = handed;
             const double start = t_source > handed ? t_source : handed;
-            t_source = start + (L - k);
+            t_source = start + (L - k) * w[r];
             T_out[r] = k;
             finish_out[r] = t_source;
         }
@@ -120,7 +131,7 @@ int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, d
             if (r >= 0) {
                 core.with_source[r] = 1;
                 T_out[r] = core.done[r];
-                source_free = t + (L - core.done[r]);
+                source_free = t + (L - core.done[r]) * w[r];
                 fin[r] = source_free;
             }
         }
@@ -128,7 +139,7 @@ int bz_zz_simulate(int policy, int n_layers, int n_requests, double load_time, d
             const int r = core.pick_target(resident_at(t, load_time, L));
             if (r >= 0) {
                 target_req = r;
-                target_end = t + 1;
+                target_end = t + w[r];
             }
         }
         double nxt = -1;

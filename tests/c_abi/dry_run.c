@@ -75,6 +75,12 @@ int main(void) {
         CHECK(bz_zz_simulate(BZ_ZZ_BEST_EFFORT, 7, 7, 6.0, 1.0, T, fin) == BZ_OK);
         CHECK(T[0] == 1 && T[5] == 1 && fin[5] == 37.0);
         CHECK(bz_zz_simulate(2, 7, 7, 6.0, 1.0, T, fin) == BZ_EINVAL);
+        {   /* a time per layer and request (section 5.4): 4 layers, one every 3, source free at 2, times (1, 2) */
+            const double w[2] = {1.0, 2.0}, bad[2] = {1.0, 0.0};
+            CHECK(bz_zz_simulate_weighted(BZ_ZZ_ZIGZAG, 4, 2, 3.0, 2.0, w, T, fin) == BZ_OK);
+            CHECK(T[0] == 1 && T[1] == 2 && fin[0] == 5.0 && fin[1] == 9.0);
+            CHECK(bz_zz_simulate_weighted(BZ_ZZ_ZIGZAG, 4, 2, 3.0, 2.0, bad, T, fin) == BZ_EINVAL);
+        }
     }
     {   /* scale plan: one source, two spare nodes under the same leaf -> one chain S -> T1 -> T2, slower target last */
         bz_plan_node nodes[3];

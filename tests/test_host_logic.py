@@ -217,6 +217,30 @@ def test_scheduler_decisions_match_the_oracle_in_virtual_time():
     assert lib.bz_zz_create(None, None, 0, C.byref(C.c_void_p())) == -1
 
 
+def test_scheduler_decisions_with_a_time_per_layer_and_request_match_the_oracle():
+    """Section 5.4's retrofit: one layer of request r takes layer_time[r].  Times are sums and products of small
+    dyadic numbers, so both sides compute them exactly and must agree bit for bit."""
+    import random
+    from oracle import zigzag as Z
+    rnd = random.Random(5)
+    for case in range(200):
+        L, n = rnd.randint(1, 12), rnd.randint(1, 10)
+        load = rnd.choice([0.0, 0.5, 1.0, 2.25, 6.0, 40.0])
+        free = rnd.choice([0.0, 0.75, 3.0, 10.0, 100.0])
+        w = [rnd.choice([0.25, 0.5, 1.0, 1.5, 3.0, 8.0]) for _ in range(n)]
+        for policy, sim in ((B.BZ_ZZ_ZIGZAG, Z.simulate_zigzag), (B.BZ_ZZ_BEST_EFFORT, Z.simulate_best_effort)):
+            T, fin = B.zz_simulate(policy, L, n, load, free, layer_time=w)
+            want = sim(L, n, load, free, layer_time=w)
+            assert T == want.T and fin == want.finish, (case, policy, L, n, load, free, w)
+    # the hand-worked timeline of the oracle's pins, through the C ABI as well
+    assert B.zz_simulate(B.BZ_ZZ_ZIGZAG, 4, 2, 3.0, 2.0, layer_time=[1, 2]) == ([1, 2], [5.0, 9.0])
+    assert B.zz_simulate(B.BZ_ZZ_BEST_EFFORT, 4, 2, 3.0, 2.0, layer_time=[1, 2]) == ([1, 1], [5.0, 11.0])
+    # factors that are not positive, or not numbers, are refused
+    for bad in ([1.0, 0.0], [1.0, -2.0], [float("nan"), 1.0], [float("inf"), 1.0]):
+        with pytest.raises(B.BzError):
+            B.zz_simulate(B.BZ_ZZ_ZIGZAG, 4, 2, 3.0, 2.0, layer_time=bad)
+
+
 def _random_cluster(rng):
     n = int(rng.integers(2, 14))
     nodes = []
