@@ -896,10 +896,19 @@ __global__ __launch_bounds__(256, (SkCfg<RB, TB>::kPerCu)) void gemm_skinny_kern
     const int x_off = (wt * 32 * TB + lrow) * 128;
     const int w_off = kXBytes + (wf * HALF + lrow) * 128;
 
+    // Every workgroup would walk its k-tiles in the same order at about the same pace, so that at any moment the
+    // whole chip reads the same 128-byte column of thousands of weight rows; when the row pitch is a power of two
+    // those addresses differ in their high bits only and crowd onto few memory channels.  A tile therefore starts
+    // its walk tile_n / n_tiles of the way in and wraps around (a function of the shape and the tile alone, so
+    // the sum order, and with it every output bit, stays fixed).  Measured in the decode loop: gate/up of the 8B
+    // shape 50 -> 41 us, output projection of the 70B shape 32 -> 26 us, its QKV 34 -> 32 us; pitches that are
+    // no power of two, and walks of fewer than 32 tiles, gain nothing or lose 1-2 % and keep the plain order.
+    const int rot = ((K & (K - 1)) == 0 && n >= 32) ? (int)(((long long)tile_n * n) / n_tiles) : 0;
+    auto kmap = [&](int j) { const int r = j + rot; return kt0 + (r >= n ? r - n : r); };   // j-th k-tile of the walk
     // prologue: up to kStages - 1 tiles in flight
 #pragma unroll
     for (int t = 0; t < kStages - 1; ++t)
-        if (n > t) issue(kt0 + t, t);
+        if (n > t) issue(kmap(t), t);
     int cur = 0, nxt = kStages - 1;                  // stage of tile i; stage the tile requested next goes to
     for (int i = 0; i < n; ++i) {
         // tile i must have landed; the tiles requested after it (LPS loads each) may still be in flight
@@ -911,7 +920,7 @@ __global__ __launch_bounds__(256, (SkCfg<RB, TB>::kPerCu)) void gemm_skinny_kern
         else __builtin_amdgcn_s_waitcnt(sk_wait(0));
         __builtin_amdgcn_s_barrier();                              // everyone's part landed; the stage of tile i-1 is free
         __builtin_amdgcn_sched_barrier(0);
-        if (i + kStages - 1 < n) issue(kt0 + i + kStages - 1, nxt);
+        if (i + kStages - 1 < n) issue(kmap(i + kStages - 1), nxt);
         const unsigned char* st = smem_raw + cur * kStage;
         nxt = cur;
         cur = (cur + 1 == kStages) ? 0 : cur + 1;
