@@ -55,6 +55,8 @@ GEMM_SHAPES = [
     (128, 1024, 4096), (97, 688, 1024), (100, 256, 4096), (250, 512, 2048),
     # a few hundred rows, fewer tiles than CUs: every tile of the large-tile kernel split over K
     (200, 4096, 2048), (600, 1376, 4096),
+    # decode-sized with a power-of-two row pitch and 32 k-tiles per workgroup: tiles start their walk over K at different places
+    (40, 7168, 4096), (150, 7168, 4096),
 ]
 
 
