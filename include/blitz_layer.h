@@ -190,6 +190,15 @@ int bz_load_layer(bz_instance* inst, int layer, const void* host, size_t n);
  * host two concurrent transfers ran at 46 GB/s where one kept 55.8.  A caller that cares measures
  * both on its own buffers (bench.py does, during warm-up).  BZ_EINVAL for any other n. */
 int bz_set_ingest_streams(bz_instance* inst, int n);
+/* Makes `stream` (a hipStream_t of the caller's, distinct from the instance's compute and copy streams) the
+ * second ingest stream, in place of one the library would create; the caller keeps it alive until
+ * bz_destroy and owns it afterwards.  For processes that run several instances: a process has few hardware
+ * queues, streams are dealt onto them in creation order, and an ingest stream that lands on the compute
+ * stream's queue serialises copies and kernels; a caller that creates its streams once, early, and lends
+ * them to every instance keeps the assignment it has measured.  Waits for transfers still on a stream it
+ * replaces.  Does not change the number of streams in use (bz_set_ingest_streams).  BZ_ESTATE on a dry-run
+ * instance. */
+int bz_lend_second_copy_stream(bz_instance* inst, void* stream);
 /* Same, from a device buffer (a resident peer's copy: one hop of section 5.1's forwarding chain). */
 int bz_load_layer_from_device(bz_instance* inst, int layer, const void* dev, size_t n);
 /* Parallel sharded transfer (section 5.1, the optimisation that sends the shards of a layer from

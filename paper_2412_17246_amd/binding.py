@@ -115,6 +115,7 @@ SIGNATURES = {
     "bz_load_layer": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
     "bz_load_layer_from_device": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
     "bz_set_ingest_streams": (C.c_int, [_P, C.c_int]),
+    "bz_lend_second_copy_stream": (C.c_int, [_P, _P]),
     "bz_load_layer_sharded": (C.c_int, [_P, C.c_int, C.POINTER(bz_shard), C.c_int]),
     "bz_plan_generate": (C.c_int, [C.POINTER(bz_plan_node), C.c_int, C.c_int, C.c_double, C.c_int, C.c_double,
                                    C.POINTER(bz_plan_hop), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int),
@@ -342,6 +343,11 @@ class Instance:
     # -- ingest
     def set_ingest_streams(self, n: int) -> None:
         self._check(self.lib.bz_set_ingest_streams(self.handle, n), "bz_set_ingest_streams")
+
+    def lend_second_copy_stream(self, stream) -> None:
+        """A torch stream of the caller's as the second ingest stream (kept alive by this object)."""
+        self._check(self.lib.bz_lend_second_copy_stream(self.handle, stream.cuda_stream), "bz_lend_second_copy_stream")
+        self.copy_stream2 = stream
 
     def load_layer(self, layer: int, pinned) -> None:
         self._check(self.lib.bz_load_layer(self.handle, layer, _ptr(pinned), pinned.numel()), "bz_load_layer")

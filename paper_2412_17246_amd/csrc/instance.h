@@ -79,6 +79,7 @@ struct bz_instance {
     // second copy stream (always the library's own, created by the first bz_set_ingest_streams(2)): a layer's
     // tensor groups are then cut in two halves, one per stream
     hipStream_t copy2 = nullptr;
+    bool own_copy2 = false;
     int ingest_streams = 1;
     unsigned char* weights = nullptr;
     unsigned char* kv = nullptr;

@@ -327,7 +327,7 @@ int bz_destroy(bz_instance* I) {
     if (!I->dry) {
         if (I->compute) (void)hipStreamSynchronize(I->compute);
         if (I->copy) (void)hipStreamSynchronize(I->copy);
-        if (I->copy2) { (void)hipStreamSynchronize(I->copy2); (void)hipStreamDestroy(I->copy2); }
+        if (I->copy2) { (void)hipStreamSynchronize(I->copy2); if (I->own_copy2) (void)hipStreamDestroy(I->copy2); }
         for (hipEvent_t e : I->ev) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : I->ev_part) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : I->ev_part2) if (e) (void)hipEventDestroy(e);
@@ -440,8 +440,26 @@ int bz_set_ingest_streams(bz_instance* I, int n) {
     if (!I || (n != 1 && n != 2)) return BZ_EINVAL;
     // the second stream exists only for instances that ask for it: a process has few hardware queues, and a
     // split pair of instances would otherwise hold eight streams between them
-    if (n == 2 && !I->dry && !I->copy2) HIP_TRY(hipStreamCreateWithFlags(&I->copy2, hipStreamNonBlocking));
+    if (n == 2 && !I->dry && !I->copy2) {
+        HIP_TRY(hipStreamCreateWithFlags(&I->copy2, hipStreamNonBlocking));
+        I->own_copy2 = true;
+    }
     I->ingest_streams = n;
+    return BZ_OK;
+}
+
+int bz_lend_second_copy_stream(bz_instance* I, void* stream) {
+    if (!I || !stream) return BZ_EINVAL;
+    if (I->dry) return BZ_ESTATE;
+    const hipStream_t st = (hipStream_t)stream;
+    if (st == I->copy || st == I->compute) return BZ_EINVAL;
+    if (I->copy2 == st) return BZ_OK;
+    if (I->copy2) {                     // halves of earlier layers may still travel on the stream being replaced
+        HIP_TRY(hipStreamSynchronize(I->copy2));
+        if (I->own_copy2) HIP_TRY(hipStreamDestroy(I->copy2));
+    }
+    I->copy2 = st;
+    I->own_copy2 = false;
     return BZ_OK;
 }
 

@@ -189,6 +189,48 @@ def test_ingest_sources_must_be_page_locked(torch):
     inst.close()
 
 
+def test_second_ingest_stream_lent_by_the_caller(torch):
+    """Two instances take the same caller-made stream as their second ingest stream: layers loaded over two streams
+    arrive bit for bit, the stream outlives the instances, and the instance's own streams are refused."""
+    s = W.CONFIGS["tiny"]
+    lent = torch.cuda.Stream()
+    blobs, insts = [], []
+    for k in range(2):
+        inst = U.make_instance(s, max_seqs=1, max_seq_len=64, max_tokens=16, kv_tokens=64)
+        inst.lend_second_copy_stream(lent)
+        inst.lend_second_copy_stream(lent)                   # again: nothing to do
+        inst.set_ingest_streams(2)
+        for bad in (inst.copy_stream, inst.compute_stream):
+            with pytest.raises(Exception) as ei:
+                inst.lend_second_copy_stream(bad)
+            assert "BZ_EINVAL" in str(ei.value)
+        insts.append(inst)
+    for l in range(s.L):
+        blob = insts[0].pack_layer(W.layer_weights_bits(s, l))
+        blobs.append(blob)
+        for inst in insts:
+            inst.load_layer(l, inst.pinned_blob(blob))
+    for inst in insts:
+        for l in range(s.L):
+            inst.wait_layer(l)
+            assert np.array_equal(inst.readback_layer(l), blobs[l])
+        assert inst.frontier() == s.L
+    # a stream the library made itself is replaced by the lent one (and destroyed); loading goes on over the new one
+    own = U.make_instance(s, max_seqs=1, max_seq_len=64, max_tokens=16, kv_tokens=64)
+    own.set_ingest_streams(2)
+    own.load_layer(0, own.pinned_blob(blobs[0]))
+    own.lend_second_copy_stream(lent)                        # waits for the halves still on the old stream
+    own.load_layer(1, own.pinned_blob(blobs[1]))
+    own.sync()
+    assert np.array_equal(own.readback_layer(0), blobs[0]) and np.array_equal(own.readback_layer(1), blobs[1])
+    for inst in insts + [own]:
+        inst.close()
+    with torch.cuda.stream(lent):                            # still a working stream
+        t = torch.ones(8, device="cuda") * 3
+    lent.synchronize()
+    assert float(t.sum()) == 24.0
+
+
 def test_batch_storage_bound_holds_for_the_extreme_batches(torch):
     """bz_batch_storage_bytes(max_seqs, max_tokens, max_seq_len) is enough for every batch within those limits:
     all sequences decoding on caches of the maximum length, one token per sequence of prefill, one long

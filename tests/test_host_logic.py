@@ -178,6 +178,8 @@ def test_frontier_and_argument_checks_without_a_gpu(dry):
     assert lib.bz_load_layer(h, 0, buf.ctypes.data, buf.size) == -8            # dry run: validated, not enqueued
     assert lib.bz_readback_layer(h, 0, buf.ctypes.data) == -4
     assert lib.bz_export_boundary(h, 1, 65, 1, 0) == -7                        # T above max_tokens
+    assert lib.bz_lend_second_copy_stream(h, None) == -1 and lib.bz_lend_second_copy_stream(None, 1) == -1
+    assert lib.bz_lend_second_copy_stream(h, 1) == -8                          # dry run: no streams at all
     st = dry.stats()
     assert st["bytes_ingested"] == 0 and st["frontier"] == 0
 
