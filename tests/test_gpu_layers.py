@@ -252,6 +252,42 @@ def test_mixed_ragged_batch(torch, fp32, shape):
             assert U.rel_err(got[a:b], want[a:b]) <= tol, (i, seqs[i])
 
 
+def _random_case(case):
+    """A seeded random decoder shape (head size, heads per group, widths that are multiples of 8 only) and batch."""
+    import random
+    rnd = random.Random(case)
+    d = rnd.choice([64, 128])
+    Hkv = rnd.choice([1, 2, 3, 4, 6])
+    Hq = Hkv * rnd.choice([1, 2, 4, 8])
+    s = W.DecoderShape(f"r{case}", L=rnd.choice([1, 2]), H=8 * rnd.randint(8, 160), Hq=Hq, Hkv=Hkv, d=d,
+                       F=8 * rnd.randint(8, 200), rope_base=rnd.choice([10000.0, 500000.0]), seed=1000 + case)
+    kind = rnd.choice(["mixed", "decode", "prefill", "small"])
+    seqs = []
+    for _ in range(rnd.randint(1, 12)):
+        if kind == "decode":
+            seqs.append((1, rnd.choice([0, 1, 31, 255, 256, 257, rnd.randint(0, 1500)])))
+        elif kind == "prefill":
+            seqs.append((rnd.choice([2, 17, 128, 129, rnd.randint(2, 400)]), rnd.choice([0, 0, rnd.randint(0, 300)])))
+        elif kind == "small":
+            seqs.append((rnd.choice([0, 1, 1, 2, 5]), rnd.choice([0, 3, 40, 300])))
+        else:
+            seqs.append((rnd.choice([0, 1, 1, 1, 3, 64, rnd.randint(1, 300)]),
+                         rnd.choice([0, 0, 15, 16, 255, 256, rnd.randint(0, 900)])))
+    seqs = [(n, b if (n or b) else 1) for n, b in seqs]      # _mixed_case's arena has room for one empty sequence
+    if sum(n for n, _ in seqs) == 0:
+        seqs.append((1, 7))
+    return s, seqs
+
+
+@pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
+@pytest.mark.parametrize("case", range(16))
+def test_random_shapes_and_batches(torch, fp32, case):
+    # widths, head counts and length mixes nobody picked by hand (three and six kv heads, widths like 8 * 37)
+    shape, seqs = _random_case(case)
+    got, want, _ = _mixed_case(torch, shape, fp32, seqs)
+    assert U.rel_err(got, want) <= _tol(fp32), (shape, seqs)
+
+
 @pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
 @pytest.mark.parametrize("shape", [MIX, G8], ids=lambda s: s.name)
 def test_small_mixed_batch_takes_the_decode_sized_kernels(torch, fp32, shape):
