@@ -98,6 +98,20 @@ def test_gemm(torch, fp32, mode, M, N, K):
         assert U.rel_err(U.from_device(c2), want) <= U.BF16_TOL
 
 
+@pytest.mark.parametrize("case", range(10))
+def test_gemm_random_problems(torch, case):
+    """Seeded random problems: any N (odd ones take the element-wise store path), K any multiple of 8, row counts on
+    both sides of every kernel boundary; all three modes, both builds."""
+    import random
+    rnd = random.Random(case)
+    M = rnd.choice([1, 2, 63, 64, 65, 255, 256, 257, rnd.randint(1, 900)])
+    N = rnd.choice([rnd.randint(1, 1500), 4 * rnd.randint(1, 400), 8 * rnd.randint(1, 300), 256 * rnd.randint(1, 6)])
+    K = 8 * rnd.choice([rnd.randint(1, 300), 8 * rnd.randint(1, 64)])
+    for mode in (0, 1, 2):
+        for fp32 in (False, True):
+            test_gemm(torch, fp32, mode, M, N, K)
+
+
 def test_gemm_residual_in_place_and_identity(torch):
     from paper_2412_17246_amd import op_gemm
     M, N = 150, 256
