@@ -166,3 +166,53 @@ def test_empty_ranges_and_single_token(torch):
         inst.run_layers(0, 2, inst.batch([0, 1], [1], [0]), x)     # slot never reserved
     assert "BZ_ESTATE" in str(ei.value)
     inst.close()
+
+
+def test_plain_c_program_streams_layers_and_runs_them(torch, tmp_path):
+    """tests/c_abi/gpu_run.c, compiled with gcc as C99 against include/blitz_layer.h and the HIP runtime's C API: no
+    Python and no PyTorch in its process, streams and arenas made by the library.  It streams the layers of a small
+    GQA shape in, runs a prompt behind the frontier and one decode step, reads every layer back; its output file is
+    compared with the oracle here."""
+    import os
+    import shutil
+    import subprocess
+    from oracle import decoder as O
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2412_17246_amd")
+    exe = str(tmp_path / "gpu_run")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(root, "include"),
+           "-isystem", "/opt/rocm/include", os.path.join(root, "tests", "c_abi", "gpu_run.c"), "-o", exe,
+           "-L", pkg, "-l:libblitzlayer.so", "-L", "/opt/rocm/lib", "-lamdhip64",
+           "-Wl,-rpath," + pkg, "-Wl,-rpath,/opt/rocm/lib"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+
+    s = W.DecoderShape("cprog", L=3, H=384, Hq=8, Hkv=2, d=64, F=520, rope_base=10000.0, seed=77)
+    T = 150                                                    # two query tiles, the second ragged
+    probe = B.Instance(s, max_seqs=1, max_seq_len=8, max_tokens=8, kv_tokens=32, dry_run=True)
+    bits = {l: W.layer_weights_bits(s, l) for l in range(s.L)}
+    blobs = [probe.pack_layer(bits[l]) for l in range(s.L)]
+    probe.close()
+    xbits = W.hidden_bits(s, T + 1, step=9, scale=1.0 / 16)    # rows 0..T-1: the prompt; row T: the decode step's input
+    src, dst = tmp_path / "in.bin", tmp_path / "out.bin"
+    with open(src, "wb") as f:
+        f.write(np.array([s.L, s.H, s.Hq, s.Hkv, s.d, s.F, T], dtype=np.int32).tobytes())
+        f.write(np.array([s.eps, s.rope_base], dtype=np.float32).tobytes())
+        for b in blobs:
+            f.write(b.tobytes())
+        f.write(np.ascontiguousarray(xbits, dtype=np.uint16).tobytes())
+    run = subprocess.run([exe, str(src), str(dst)], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, run.stdout + run.stderr
+    got = U.f64(np.fromfile(dst, dtype=np.uint16).reshape(T + 1, s.H))
+
+    os_ = U.oracle_shape(s)
+    wts = {l: U.oracle_weights(bits[l]) for l in range(s.L)}
+    okv = O.OracleKV()
+    x = U.f64(xbits)
+    want_p = O.run_layers(os_, wts, 0, s.L, x[:T], O.OracleBatch([0, T], [0], [0]), okv)
+    want_d = O.run_layers(os_, wts, 0, s.L, x[T:], O.OracleBatch([0, 1], [0], [T]), okv)
+    assert U.rel_err(got[:T], want_p) <= U.BF16_TOL
+    assert U.rel_err(got[T:], want_d) <= U.BF16_TOL
+    U.assert_rms(got[:T], want_p, U.RMS_BF16)
