@@ -9,10 +9,12 @@
  *        L layer blobs of bz_sizes.layer_bytes bytes; T*H bf16 hidden states (prefill); H bf16 hidden states (decode)
  * <out>: T*H bf16 (prefill output), H bf16 (decode output)
  * Every layer is also read back and compared with what was sent.  Exit status 0 = everything succeeded. */
+#define _POSIX_C_SOURCE 199309L
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <time.h>
 
 #include <hip/hip_runtime_api.h>
 
@@ -38,6 +40,12 @@
 
 static int read_all(FILE* f, void* dst, size_t n) { return fread(dst, 1, n, f) == n ? 0 : 1; }
 
+static double now_ms(void) {
+    struct timespec t;
+    clock_gettime(CLOCK_MONOTONIC, &t);
+    return (double)t.tv_sec * 1e3 + (double)t.tv_nsec * 1e-6;
+}
+
 int main(int argc, char** argv) {
     int32_t hdr[7];
     float fl[2];
@@ -50,6 +58,8 @@ int main(int argc, char** argv) {
     FILE *in, *out;
     int l, T;
     size_t row_bytes;
+    const double t_start = now_ms();
+    double t_runtime, t_create0, t_created, t_load0, t_done;
 
     if (argc != 3) { fprintf(stderr, "usage: %s <in> <out>\n", argv[0]); return 2; }
     in = fopen(argv[1], "rb");
@@ -65,6 +75,8 @@ int main(int argc, char** argv) {
     if (sz.act_elem_bytes != 2) { fprintf(stderr, "this program feeds bf16 activations\n"); return 2; }
     row_bytes = (size_t)cfg.hidden * 2;
 
+    HIP(hipFree(NULL));                               /* brings the runtime up */
+    t_runtime = now_ms();
     HIP(hipHostMalloc((void**)&blobs, sz.layer_bytes * (size_t)cfg.n_layers, hipHostMallocDefault));
     HIP(hipHostMalloc((void**)&back, sz.layer_bytes, hipHostMallocDefault));
     HIP(hipHostMalloc(&x_host, row_bytes * (size_t)(T + 1), hipHostMallocDefault));
@@ -76,7 +88,9 @@ int main(int argc, char** argv) {
     HIP(hipMalloc(&x_dev, row_bytes * (size_t)(T + 1)));
     HIP(hipMemcpy(x_dev, x_host, row_bytes * (size_t)(T + 1), hipMemcpyHostToDevice));
 
+    t_create0 = now_ms();
     BZ(bz_create(&cfg, &inst));
+    t_created = now_ms();
     BZ(bz_kv_reserve(inst, 0, T + 1));
     {
         int32_t q_start[2], slot[1] = {0}, before[1] = {0};
@@ -92,10 +106,12 @@ int main(int argc, char** argv) {
         fprintf(stderr, "a run over layers that were never requested must be refused\n");
         return 1;
     }
+    t_load0 = now_ms();
     for (l = 0; l < cfg.n_layers; ++l) BZ(bz_load_layer(inst, l, blobs + sz.layer_bytes * (size_t)l, sz.layer_bytes));
     BZ(bz_run_layers(inst, 0, cfg.n_layers, prefill, x_dev, 0));
     BZ(bz_run_layers(inst, 0, cfg.n_layers, decode, (unsigned char*)x_dev + row_bytes * (size_t)T, 0));
     BZ(bz_sync(inst));
+    t_done = now_ms();
     if (bz_frontier(inst) != cfg.n_layers) { fprintf(stderr, "frontier %d\n", bz_frontier(inst)); return 1; }
     for (l = 0; l < cfg.n_layers; ++l) {
         BZ(bz_readback_layer(inst, l, back));
@@ -118,5 +134,7 @@ int main(int argc, char** argv) {
     HIP(hipHostFree(back));
     HIP(hipHostFree(blobs));
     printf("ran %d layers over %d prompt tokens and one decode step\n", (int)cfg.n_layers, T);
+    printf("runtime up after %.0f ms; bz_create %.1f ms; first load request to both outputs %.1f ms (first use of the "
+           "kernels included)\n", t_runtime - t_start, t_created - t_create0, t_done - t_load0);
     return 0;
 }

@@ -205,6 +205,7 @@ def test_plain_c_program_streams_layers_and_runs_them(torch, tmp_path):
         f.write(np.ascontiguousarray(xbits, dtype=np.uint16).tobytes())
     run = subprocess.run([exe, str(src), str(dst)], capture_output=True, text=True, timeout=120)
     assert run.returncode == 0, run.stdout + run.stderr
+    print(run.stdout)
     got = U.f64(np.fromfile(dst, dtype=np.uint16).reshape(T + 1, s.H))
 
     os_ = U.oracle_shape(s)
