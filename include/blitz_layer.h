@@ -201,6 +201,14 @@ int bz_set_ingest_streams(bz_instance* inst, int n);
 int bz_lend_second_copy_stream(bz_instance* inst, void* stream);
 /* Same, from a device buffer (a resident peer's copy: one hop of section 5.1's forwarding chain). */
 int bz_load_layer_from_device(bz_instance* inst, int layer, const void* dev, size_t n);
+/* Serial forwarding chain (section 5.1: a node passes layer k on while it receives layer k + 1): loads layer
+ * `layer` from the copy that `peer`, an instance of the same shape on the same GPU, holds or is still receiving.
+ * Returns at once; on the device the transfer starts when the peer's layer has landed, so a chain
+ * S -> T1 -> T2 is set up by requesting every layer on T1 and then on T2 without waiting in between.  The peer
+ * must keep the layer (no bz_unload_layer, no bz_destroy) until it is resident here.  BZ_ENOTLOADED if the
+ * peer's layer was never requested, BZ_ESTATE if it is in the failed state or either instance is a dry run,
+ * BZ_EINVAL for peer == inst or another shape; otherwise as bz_load_layer. */
+int bz_load_layer_from_peer(bz_instance* inst, int layer, bz_instance* peer);
 /* Parallel sharded transfer (section 5.1, the optimisation that sends the shards of a layer from
  * several sources at once): the layer's bytes arrive as n_shards <= BZ_MAX_SHARDS contiguous pieces, each from its
  * own source buffer, spread over two extra copy streams so that transfers from different sources

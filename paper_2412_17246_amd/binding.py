@@ -114,6 +114,7 @@ SIGNATURES = {
     "bz_sync": (C.c_int, [_P]),
     "bz_load_layer": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
     "bz_load_layer_from_device": (C.c_int, [_P, C.c_int, _P, C.c_size_t]),
+    "bz_load_layer_from_peer": (C.c_int, [_P, C.c_int, _P]),
     "bz_set_ingest_streams": (C.c_int, [_P, C.c_int]),
     "bz_lend_second_copy_stream": (C.c_int, [_P, _P]),
     "bz_load_layer_sharded": (C.c_int, [_P, C.c_int, C.POINTER(bz_shard), C.c_int]),
@@ -352,6 +353,11 @@ class Instance:
     def load_layer(self, layer: int, pinned) -> None:
         self._check(self.lib.bz_load_layer(self.handle, layer, _ptr(pinned), pinned.numel()), "bz_load_layer")
         self._keep[layer] = [pinned]
+
+    def load_layer_from_peer(self, layer: int, peer: "Instance") -> None:
+        """One hop of a forwarding chain: the layer comes from `peer`'s copy as soon as that has landed."""
+        self._check(self.lib.bz_load_layer_from_peer(self.handle, layer, peer.handle), "bz_load_layer_from_peer")
+        self._keep[layer] = [peer]
 
     def load_layer_from_device(self, layer: int, dev) -> None:
         self._check(self.lib.bz_load_layer_from_device(self.handle, layer, _ptr(dev), dev.numel()),

@@ -206,7 +206,8 @@ bool is_pinned_host(const void* p) {
     return a.type == hipMemoryTypeHost;
 }
 
-int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpyKind kind) {
+// `after` (optional): an event of another stream that must have completed before the first byte is read
+int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpyKind kind, hipEvent_t after = nullptr) {
     if (!I || !src) return BZ_EINVAL;
     if (layer < 0 || layer >= I->sh.L || n != I->sz.layer_bytes) return BZ_EINVAL;
     if (I->state[layer] != kNone) return BZ_EBUSY;
@@ -228,6 +229,10 @@ int enqueue_copy(bz_instance* I, int layer, const void* src, size_t n, hipMemcpy
     const size_t ends[4] = {I->lay.wo, I->lay.wg, I->lay.wd, n};
     auto enqueue = [&]() -> hipError_t {
         hipError_t e = hipSuccess;
+        if (after) {
+            if ((e = hipStreamWaitEvent(I->copy, after, 0)) != hipSuccess) return e;
+            if (two && (e = hipStreamWaitEvent(I->copy2, after, 0)) != hipSuccess) return e;
+        }
         size_t start = 0;
         for (int part = 0; part < 4; ++part) {
             const size_t mid = start + ((ends[part] - start) / 2 + 255) / 256 * 256;
@@ -469,6 +474,19 @@ int bz_load_layer(bz_instance* I, int layer, const void* host, size_t n) {
 
 int bz_load_layer_from_device(bz_instance* I, int layer, const void* dev, size_t n) {
     return enqueue_copy(I, layer, dev, n, hipMemcpyDeviceToDevice);
+}
+
+int bz_load_layer_from_peer(bz_instance* I, int layer, bz_instance* peer) {
+    if (!I || !peer || I == peer) return BZ_EINVAL;
+    if (layer < 0 || layer >= I->sh.L || layer >= peer->sh.L) return BZ_EINVAL;
+    if (I->sz.layer_bytes != peer->sz.layer_bytes || I->sh.H != peer->sh.H || I->sh.F != peer->sh.F ||
+        I->sh.Hq != peer->sh.Hq || I->sh.Hkv != peer->sh.Hkv || I->sh.d != peer->sh.d)
+        return BZ_EINVAL;
+    if (I->dry || peer->dry) return BZ_ESTATE;
+    if (peer->state[layer] == kNone) return BZ_ENOTLOADED;
+    if (peer->state[layer] == kFailed) return BZ_ESTATE;
+    // the peer's layer event lies behind all of the layer's bytes, on whichever streams they travelled
+    return enqueue_copy(I, layer, layer_ptr(peer, layer), I->sz.layer_bytes, hipMemcpyDeviceToDevice, peer->ev[layer]);
 }
 
 int bz_load_layer_sharded(bz_instance* I, int layer, const bz_shard* shards, int n_shards) try {

@@ -54,6 +54,58 @@ def test_device_resident_source_and_reload(torch):
     inst.close()
 
 
+@pytest.mark.parametrize("streams", [1, 2])
+def test_forwarding_chain_of_three_instances(torch, streams):
+    """Section 5.1, serial forwarding chain S -> T1 -> T2 on one GPU: T1 receives every layer from page-locked host
+    memory, T2 takes each layer from T1's copy as it lands, while T1 is receiving the next ones; nothing waits on
+    the host while the chain is set up.  T2 executes a batch behind its own frontier; its weights are T1's bytes and
+    its output is that of an instance loaded directly."""
+    s = W.DecoderShape("chain", L=6, H=512, Hq=8, Hkv=2, d=64, F=1024, rope_base=10000.0, seed=88)
+    mk = lambda: U.make_instance(s, max_seqs=1, max_seq_len=96, max_tokens=80, kv_tokens=96, chunk_bytes=256 << 10)
+    t1, t2, ref = mk(), mk(), mk()
+    other = U.make_instance(TINY, max_seqs=1, max_seq_len=32, max_tokens=8, kv_tokens=32)
+    for inst in (t1, t2):
+        inst.set_ingest_streams(streams)
+    blobs = [t1.pack_layer(W.layer_weights_bits(s, l)) for l in range(s.L)]
+    pinned = [t1.pinned_blob(b) for b in blobs]
+    for bad, code in ((t2, "BZ_EINVAL"), (other, "BZ_EINVAL"), (t1, "BZ_ENOTLOADED")):   # itself; another shape; nothing requested yet
+        with pytest.raises(Exception) as ei:
+            t2.load_layer_from_peer(0, bad)
+        assert code in str(ei.value)
+    xbits = W.hidden_bits(s, 80, step=4, scale=1.0 / 16)
+    x2, xr = U.to_device(xbits, False), U.to_device(xbits, False)
+    for inst in (t2, ref):
+        inst.kv_reserve(0, 80)
+    torch.cuda.synchronize()
+    for l in range(s.L):
+        t1.load_layer(l, pinned[l])
+        t2.load_layer_from_peer(l, t1)
+    t2.run_layers(0, s.L, t2.batch([0, 80], [0], [0]), x2, after_current_stream=False)
+    seen = []
+    for _ in range(50):                                   # T2 never holds a layer T1 does not hold yet
+        f2 = t2.frontier()
+        f1 = t1.frontier()
+        assert f2 <= f1
+        seen.append((f1, f2))
+        if f2 == s.L:
+            break
+    t2.sync()
+    t1.sync()
+    assert t1.frontier() == s.L and t2.frontier() == s.L
+    for l in range(s.L):
+        assert np.array_equal(t2.readback_layer(l), blobs[l])
+    with pytest.raises(Exception) as ei:
+        t2.load_layer_from_peer(0, t1)                      # already resident here
+    assert "BZ_EBUSY" in str(ei.value)
+    for l in range(s.L):
+        ref.load_layer(l, pinned[l])
+    ref.run_layers(0, s.L, ref.batch([0, 80], [0], [0]), xr, after_current_stream=False)
+    ref.sync()
+    assert torch.equal(x2.view(torch.int16), xr.view(torch.int16))
+    for inst in (t2, t1, ref, other):
+        inst.close()
+
+
 @pytest.mark.parametrize("n_shards", [1, 3, 4, 16])
 def test_sharded_ingest_is_byte_exact_and_ready_only_when_all_shards_landed(torch, n_shards):
     """Section 5.1, parallel sharded transfer: uneven shards, given out of order, from a mix of pinned

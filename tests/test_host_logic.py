@@ -180,6 +180,7 @@ def test_frontier_and_argument_checks_without_a_gpu(dry):
     assert lib.bz_export_boundary(h, 1, 65, 1, 0) == -7                        # T above max_tokens
     assert lib.bz_lend_second_copy_stream(h, None) == -1 and lib.bz_lend_second_copy_stream(None, 1) == -1
     assert lib.bz_lend_second_copy_stream(h, 1) == -8                          # dry run: no streams at all
+    assert lib.bz_load_layer_from_peer(h, 0, h) == -1 and lib.bz_load_layer_from_peer(h, 0, None) == -1
     st = dry.stats()
     assert st["bytes_ingested"] == 0 and st["frontier"] == 0
 
