@@ -130,6 +130,44 @@ def test_7b_two_layer_cut_with_the_second_layer_streamed_behind_the_first(torch)
     assert err <= U.BF16_TOL, err
 
 
+def test_7b_forwarding_chain_costs_one_hop_not_one_model(torch):
+    """Section 5.1: in a chain S -> T1 -> T2 a node forwards layer k while it receives layer k + 1, so the last
+    node lags the first by one hop, not by the model.  Four 405 MB layers of the 7B shape: T1 from page-locked host
+    memory, T2 from T1's copy; every layer of T2 lands after T1's and well within the time T1 needs for its next
+    layer; the bytes are T1's."""
+    base = W.CONFIGS["7b"]
+    s = W.DecoderShape(base.name, 4, base.H, base.Hq, base.Hkv, base.d, base.F, base.eps, base.rope_base, base.seed)
+    t1 = U.make_instance(s, max_seqs=1, max_seq_len=64, max_tokens=16, kv_tokens=64)
+    t2 = U.make_instance(s, max_seqs=1, max_seq_len=64, max_tokens=16, kv_tokens=64)
+    rng = np.random.default_rng(12)
+    pinned = []
+    for l in range(s.L):
+        p = torch.empty(t1.layer_bytes, dtype=torch.uint8, pin_memory=True)
+        p.numpy()[:] = rng.integers(0, 256, t1.layer_bytes, dtype=np.uint8)
+        pinned.append(p)
+    # warm the copy paths once (the first transfer of a process carries one-time costs), then start over
+    t1.load_layer(0, pinned[0]); t2.load_layer_from_peer(0, t1); t2.sync(); t1.sync()
+    t2.unload_layer(0); t1.unload_layer(0)
+    torch.cuda.synchronize()
+    t1.reset_clock(); t2.reset_clock()
+    for l in range(s.L):
+        t1.load_layer(l, pinned[l])
+        t2.load_layer_from_peer(l, t1)
+    t2.sync(); t1.sync()
+    r1 = [t1.layer_ready_ms(l) for l in range(s.L)]
+    r2 = [t2.layer_ready_ms(l) for l in range(s.L)]
+    per_layer = (r1[-1] - r1[0]) / (s.L - 1)                  # what T1 needs per layer from the host: about 7 ms
+    print(f"T1 layers resident at {[round(v, 2) for v in r1]} ms, T2 at {[round(v, 2) for v in r2]} ms")
+    assert 3.0 < per_layer < 30.0, r1
+    for l in range(s.L):
+        lag = r2[l] - r1[l]
+        assert -0.2 <= lag < 0.5 * per_layer, (l, r1, r2)     # the two clocks start some tens of microseconds apart
+    assert r2[-1] - r1[-1] < 0.1 * (r1[-1] - r1[0] + per_layer), (r1, r2)    # the whole chain: one short hop behind
+    for l in (0, s.L - 1):
+        assert np.array_equal(t2.readback_layer(l), pinned[l].numpy())
+    t2.close(); t1.close()
+
+
 def test_8b_gqa_decode_step_full_batch(torch):
     """64 sequences with seeded caches of length uniform[256, 4096], one decode step through one
     layer at the real shape: whole output against the oracle."""
