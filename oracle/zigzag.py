@@ -82,10 +82,25 @@ class Schedule:
 
 
 def _loaded(t: float, load_time: float, L: int) -> int:
-    """Layers resident on the target at time t."""
+    """Layers resident on the target at time t: layer k is resident from k * load_time on.  The count is settled
+    against the products k * load_time themselves (event times ARE such products; a quotient t / load_time may
+    round to just below k when t is exactly k * load_time)."""
     if load_time <= 0:
         return L
-    return min(L, int(t // load_time) + 1)
+    k = min(L, max(1, int(t // load_time) + 1))
+    while k < L and k * load_time <= t:
+        k += 1
+    while k > 1 and (k - 1) * load_time > t:
+        k -= 1
+    return k
+
+
+def _next_arrival(t: float, load_time: float, L: int):
+    """Time at which the next layer becomes resident after t, or None (all resident, or loading is instant)."""
+    if load_time <= 0:
+        return None
+    k = _loaded(t, load_time, L)          # layers 0 .. k-1 are resident, so layer k is the next to arrive
+    return k * load_time if k < L else None
 
 
 def _first_starts(spans: List[Span], n: int) -> List[float]:
@@ -148,10 +163,9 @@ def simulate_zigzag(L: int, n_requests: int, load_time: float, source_free_at: f
             cand.append(target_job[1])
         if source_free > t:
             cand.append(source_free)
-        if load_time > 0:
-            nxt = (int(t // load_time) + 1) * load_time
-            if nxt / load_time < L:
-                cand.append(nxt)
+        nxt = _next_arrival(t, load_time, L)
+        if nxt is not None:
+            cand.append(nxt)
         if source_free_at > t:
             cand.append(source_free_at)
         if not cand:
@@ -207,7 +221,7 @@ def simulate_configuration(L: int, T: List[int], load_time: float, source_free_a
         avail = _loaded(t_target, load_time, L)
         pick = next((r for r in range(n) if done[r] < T[r] and done[r] < avail), None)
         if pick is None:                       # wait for the next layer to arrive
-            t_target = (int(t_target // load_time) + 1) * load_time
+            t_target = _next_arrival(t_target, load_time, L)
             continue
         spans.append(Span(t_target, t_target + 1, "target", pick, done[pick], done[pick] + 1))
         if first_start[pick] is None:

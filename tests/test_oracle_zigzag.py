@@ -178,6 +178,23 @@ def test_invariants_with_layer_times(seed):
     _check_schedule(Z.simulate_best_effort(L, n, load, free, layer_time=w), L, n, load, w)
 
 
+@pytest.mark.parametrize("load", [8.07, 0.1, 1.0 / 3.0, 7.3, 2.7, 1e-3, 123.456])
+def test_load_times_whose_multiples_are_not_exact(load):
+    # k * load_time is then not exactly representable and t / load_time may round to either side of k: the
+    # simulations must still terminate, keep every invariant, and count layer k as resident exactly from k * load_time on
+    for L, n, free in ((32, 6, 0.0), (7, 7, 1.0), (5, 9, 2.5)):
+        z = Z.simulate_zigzag(L, n, load, free)
+        b = Z.simulate_best_effort(L, n, load, free)
+        _check_schedule(z, L, n, load)
+        _check_schedule(b, L, n, load)
+        cfg = Z.simulate_configuration(L, z.T, load, free)
+        _check_schedule(cfg, L, n, load)
+    for k in range(1, 40):
+        assert Z._loaded(k * load, load, 64) == k + 1
+        assert Z._loaded(k * load * (1 - 1e-12), load, 64) == k
+        assert Z._next_arrival(k * load, load, 64) == (k + 1) * load
+
+
 def test_limits_with_closed_forms():
     # loading never progresses beyond layer 0 within the horizon and the source is free from time 1:
     # request r is taken by the source at 1 + r*(L-1) after exactly one layer on the target
