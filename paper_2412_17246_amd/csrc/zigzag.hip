@@ -54,10 +54,17 @@ class ZzCore {
     std::vector<char> with_source;  // the source has taken the request and runs the rest
 };
 
+// Layers resident at time t (layer k from k * load_time on).  Settled against the products k * load_time
+// themselves: event times are such products, and the quotient t / load_time may round to just below k for them.
 int resident_at(double t, double load_time, int L) {
     if (load_time <= 0) return L;
-    const int k = (int)(t / load_time) + 1;
-    return k < L ? k : L;
+    const double q = t / load_time;
+    int k = q >= (double)L ? L : (int)q + 1;
+    if (k < 1) k = 1;
+    if (k > L) k = L;
+    while (k < L && (double)k * load_time <= t) ++k;
+    while (k > 1 && (double)(k - 1) * load_time > t) --k;
+    return k;
 }
 
 }  // namespace
@@ -147,8 +154,8 @@ int bz_zz_simulate_weighted(int policy, int n_layers, int n_requests, double loa
         if (target_req >= 0) consider(target_end);
         consider(source_free);
         if (load_time > 0) {
-            const double arrival = ((long long)(t / load_time) + 1) * load_time;
-            if (arrival / load_time < L) consider(arrival);
+            const int k = resident_at(t, load_time, L);      // layer k is the next to arrive
+            if (k < L) consider((double)k * load_time);
         }
         consider(source_free_at);
         if (nxt < 0) break;

@@ -235,6 +235,13 @@ def test_scheduler_decisions_with_a_time_per_layer_and_request_match_the_oracle(
             T, fin = B.zz_simulate(policy, L, n, load, free, layer_time=w)
             want = sim(L, n, load, free, layer_time=w)
             assert T == want.T and fin == want.finish, (case, policy, L, n, load, free, w)
+    # load times whose multiples are not exact in binary: both sides count residency against the same products
+    for load in (8.07, 0.1, 1.0 / 3.0, 7.3, 2.7, 1e-3, 123.456):
+        for L, n, free in ((32, 6, 0.0), (7, 7, 1.0), (5, 9, 2.5)):
+            for policy, sim in ((B.BZ_ZZ_ZIGZAG, Z.simulate_zigzag), (B.BZ_ZZ_BEST_EFFORT, Z.simulate_best_effort)):
+                T, fin = B.zz_simulate(policy, L, n, load, free)
+                want = sim(L, n, load, free)
+                assert T == want.T and fin == want.finish, (policy, L, n, load, free)
     # the hand-worked timeline of the oracle's pins, through the C ABI as well
     assert B.zz_simulate(B.BZ_ZZ_ZIGZAG, 4, 2, 3.0, 2.0, layer_time=[1, 2]) == ([1, 2], [5.0, 9.0])
     assert B.zz_simulate(B.BZ_ZZ_BEST_EFFORT, 4, 2, 3.0, 2.0, layer_time=[1, 2]) == ([1, 1], [5.0, 11.0])
