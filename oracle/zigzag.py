@@ -188,11 +188,14 @@ def simulate_best_effort(L: int, n_requests: int, load_time: float, source_free_
         spans.append(Span(t_target, t_target + k * w[r], "target", r, 0, k))
         handed = t_target + k * w[r]
         t_target = handed
+        T.append(k)
+        S.append(L - k)
+        if k == L:                               # a one-layer model: nothing is left for the source
+            finish.append(handed)
+            continue
         start = max(t_source, handed)
         spans.append(Span(start, start + (L - k) * w[r], "source", r, k, L))
         t_source = start + (L - k) * w[r]
-        T.append(k)
-        S.append(L - k)
         finish.append(t_source)
     return Schedule(T=T, S=S, finish=finish, spans=spans, first_start=_first_starts(spans, n_requests))
 

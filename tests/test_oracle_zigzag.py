@@ -195,6 +195,15 @@ def test_load_times_whose_multiples_are_not_exact(load):
         assert Z._next_arrival(k * load, load, 64) == (k + 1) * load
 
 
+def test_one_layer_model_needs_no_source():
+    # L = 1: the target runs the only layer as soon as it is resident (time 0); a source that is busy for a long time
+    # must not hold the requests back, under either policy, and gets nothing to run
+    for sim in (Z.simulate_zigzag, Z.simulate_best_effort):
+        s = sim(1, 3, 5.0, source_free_at=100.0, layer_time=[2.0, 1.0, 0.5])
+        assert s.T == [1, 1, 1] and s.S == [0, 0, 0] and s.finish == [2.0, 3.0, 3.5]
+        assert all(sp.instance == "target" for sp in s.spans)
+
+
 def test_limits_with_closed_forms():
     # loading never progresses beyond layer 0 within the horizon and the source is free from time 1:
     # request r is taken by the source at 1 + r*(L-1) after exactly one layer on the target
