@@ -112,9 +112,13 @@ int bz_zz_simulate_weighted(int policy, int n_layers, int n_requests, double loa
             if (k < 1) k = 1;
             const double handed = t_target + k * w[r];
             t_target = handed;
+            T_out[r] = k;
+            if (k == L) {                        // a one-layer model: nothing is left for the source
+                finish_out[r] = handed;
+                continue;
+            }
             const double start = t_source > handed ? t_source : handed;
             t_source = start + (L - k) * w[r];
-            T_out[r] = k;
             finish_out[r] = t_source;
         }
         return BZ_OK;

@@ -235,6 +235,16 @@ def test_scheduler_decisions_with_a_time_per_layer_and_request_match_the_oracle(
             T, fin = B.zz_simulate(policy, L, n, load, free, layer_time=w)
             want = sim(L, n, load, free, layer_time=w)
             assert T == want.T and fin == want.finish, (case, policy, L, n, load, free, w)
+    # arbitrary floating-point load times, busy times and layer times, one-layer models included
+    for case in range(400):
+        L, n = rnd.randint(1, 40), rnd.randint(1, 12)
+        load = rnd.choice([0.0, rnd.uniform(1e-3, 0.5), rnd.uniform(0.5, 20), rnd.uniform(20, 500)])
+        free = rnd.choice([0.0, rnd.uniform(0, 5), rnd.uniform(5, 300)])
+        w = [rnd.uniform(0.05, 5) for _ in range(n)] if rnd.random() < 0.6 else None
+        for policy, sim in ((B.BZ_ZZ_ZIGZAG, Z.simulate_zigzag), (B.BZ_ZZ_BEST_EFFORT, Z.simulate_best_effort)):
+            T, fin = B.zz_simulate(policy, L, n, load, free, layer_time=w)
+            want = sim(L, n, load, free, layer_time=w)
+            assert T == want.T and fin == want.finish, (case, policy, L, n, load, free, w)
     # load times whose multiples are not exact in binary: both sides count residency against the same products
     for load in (8.07, 0.1, 1.0 / 3.0, 7.3, 2.7, 1e-3, 123.456):
         for L, n, free in ((32, 6, 0.0), (7, 7, 1.0), (5, 9, 2.5)):
