@@ -339,9 +339,9 @@ void launch_attn_prefill(const act_t* qkv, act_t* out, const BatchView& bv, cons
 // per head; the combine kernel folds the chunks of a sequence in increasing chunk order, so the
 // result does not depend on scheduling.
 // ---------------------------------------------------------------------------------------------
+#ifndef BZ_FP32_DEBUG
 constexpr int kDecodeMaxG = 8;
 
-#ifndef BZ_FP32_DEBUG
 // Both products run on the matrix cores with the cache as the row operand, read from global
 // memory straight into the instructions (a lane's 16 bytes are one operand register pair):
 //   S^T[pos, g] = K[pos, :] . q[g, :]     q fills G of the 32 columns, the rest are zero;
