@@ -289,6 +289,34 @@ def test_random_shapes_and_batches(torch, fp32, case):
 
 
 @pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
+@pytest.mark.parametrize("scale", [0.0, 1e-30, 1e-6, 1e4, 1e30], ids=lambda v: f"x{v:g}")
+def test_extreme_finite_hidden_states(torch, fp32, scale):
+    # all-zero input, magnitudes at both ends of the bf16 range: nothing overflows into inf or nan on the way (the
+    # norms rescale, the softmax subtracts its maximum) and the output still follows the oracle
+    s = W.DecoderShape("ext", L=2, H=256, Hq=4, Hkv=2, d=64, F=512, rope_base=10000.0, seed=5)
+    bits = {l: W.layer_weights_bits(s, l) for l in range(s.L)}
+    inst = U.make_instance(s, max_seqs=2, max_seq_len=400, max_tokens=301, kv_tokens=480, fp32=fp32)
+    U.load_all_layers(inst, s)
+    inst.kv_reserve(0, 300)
+    inst.kv_reserve(1, 100)
+    xf = W.f32_from_bf16_bits(W.hidden_bits(s, 301, step=2)) * np.float32(scale)
+    xb = W.bf16_bits_from_f32(xf.astype(np.float32))
+    x = U.to_device(xb, fp32)
+    torch.cuda.synchronize()
+    inst.run_layers(0, s.L, inst.batch([0, 300, 301], [0, 1], [0, 0]), x)      # a 300-token prompt and a 1-token one
+    inst.sync()
+    got = U.from_device(x)
+    inst.close()
+    want = O.run_layers(U.oracle_shape(s), {l: U.oracle_weights(bits[l]) for l in range(s.L)}, 0, s.L, U.f64(xb),
+                        O.OracleBatch([0, 300, 301], [0, 1], [0, 0]), O.OracleKV())
+    assert np.isfinite(got).all()
+    if scale == 0.0:
+        assert not got.any()
+    else:
+        assert U.rel_err(got, want) <= _tol(fp32)
+
+
+@pytest.mark.parametrize("fp32", [False, True], ids=["bf16", "fp32dbg"])
 @pytest.mark.parametrize("shape", [MIX, G8], ids=lambda s: s.name)
 def test_small_mixed_batch_takes_the_decode_sized_kernels(torch, fp32, shape):
     # at most 64 rows in all, so the projections leave split-K partial sums that the rotary/append and norm
